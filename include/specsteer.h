@@ -1,0 +1,135 @@
+/*
+ * specsteer.h -- C ABI of the MI355X (gfx950) verify-and-recover block of
+ * SpecSteer's Draft-Verify-Recover protocol.
+ *
+ * One call processes one drafted block for a batch of B independent
+ * sequences (Algorithm 1, phases 2 "Ratio-Based Verification" and 3
+ * "Steering Recovery"):
+ *
+ *   for each sequence b, for t = 0 .. K_b-1 (stop at the first rejection):
+ *       alpha_t = min(1, P_LLM(y_t) / (lambda * P_SLM^-(y_t)))          (Eq. 7)
+ *       accept iff uniforms[b][t] <= alpha_t                            (Alg. 1)
+ *   n_b = index of the first rejected position, or K_b if none
+ *   h_rec = h_LLM + beta * (h_SLM^+ - h_SLM^-)   at row n_b            (Eq. 8)
+ *   next_token ~ Softmax(h_rec / T), drawn by inverse CDF in vocabulary-index
+ *       order from uniforms[b][k_max]: the first j whose inclusive cumulative
+ *       probability exceeds the uniform ("Sample y_new ~ Softmax(h_rec)").
+ *
+ * P_x = Softmax(h_x / T) over the full vocabulary.  The paper has no
+ * temperature (T = 1 is the paper); T > 0 divides all three logit tensors.
+ * When every draft token is accepted (n_b == K_b) the same recovery
+ * distribution, taken at the row after the last draft token, yields a bonus
+ * token; the paper's loop simply re-drafts there.
+ *
+ * Logit layout: three tensors G (h_LLM), S_ctx (h_SLM^+), S_noctx (h_SLM^-),
+ * each [B, k_max+1, V], vocabulary contiguous.  Row t is the next-token
+ * distribution after the prefix plus draft tokens 0..t-1, so row t scores
+ * draft[b][t] and row K_b is the bonus row.  Rows t > K_b, draft slots
+ * t >= K_b and S_ctx rows other than n_b are never read.
+ *
+ * Pointers marked "device" must be dereferenceable by the GPU the call runs
+ * on; "host" pointers are read on the CPU during the call.  No entry point
+ * takes ownership of, allocates or frees any memory; none synchronises the
+ * stream.  All work is enqueued on the given stream and the outputs are
+ * complete when the stream reaches the end of that work.
+ */
+#ifndef SPECSTEER_H
+#define SPECSTEER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SS_OK = 0,
+    SS_ERR_NULL = 1,      /* a required pointer is NULL                               */
+    SS_ERR_SHAPE = 2,     /* batch < 0, k_max < 0, vocab < 1 or above the limits      */
+    SS_ERR_DTYPE = 3,     /* dtype is not an ss_dtype                                 */
+    SS_ERR_PARAM = 4,     /* lambda, beta, temperature or flags out of range          */
+    SS_ERR_STRIDE = 5,    /* strides overlap rows or are negative                     */
+    SS_ERR_WORKSPACE = 6, /* workspace NULL, misaligned or smaller than required      */
+    SS_ERR_DEVICE = 7     /* a HIP call failed (launch error); see hipGetLastError    */
+} ss_status;
+
+typedef enum { SS_F32 = 0, SS_BF16 = 1 } ss_dtype;
+
+#define SS_MAX_K 1024        /* largest k_max                                          */
+#define SS_MAX_VOCAB (1 << 20)
+
+typedef struct {
+    int32_t batch;       /* B >= 0 (0 is a no-op)                                              */
+    int32_t k_max;       /* padded draft length, 0..SS_MAX_K; logits hold k_max+1 rows         */
+    int32_t vocab;       /* V, 1..SS_MAX_VOCAB                                                 */
+    int32_t dtype;       /* ss_dtype of all three logit tensors                                */
+    int64_t stride_b;    /* element stride between sequences; 0 => (k_max+1)*stride_t          */
+    int64_t stride_t;    /* element stride between rows;      0 => vocab. Vocab stride is 1.   */
+    float lambda;        /* verification threshold of Eq. 7; finite, > 0. Paper default 0.5    */
+    float beta;          /* steering-recovery strength of Eq. 8; finite. Paper default 1.0     */
+    float temperature;   /* T; finite, > 0. 1.0 reproduces the paper                           */
+    uint32_t flags;      /* must be 0                                                          */
+} ss_params;
+
+/*
+ * Bytes of device scratch specsteer_verify_block needs for these params
+ * (depends on batch, k_max, vocab and dtype only).  Returns 0 if params is
+ * NULL or its shape fields are invalid.  Host call, no GPU work.
+ */
+size_t specsteer_workspace_bytes(const ss_params *params);
+
+/*
+ * The block (Algorithm 1 phases 2-3, Eq. 7, Eq. 8; see the top of this file).
+ *
+ *   G, S_ctx, S_noctx  device, [B, k_max+1, V] logits of params->dtype.  The fast
+ *                      path needs all three base pointers 16-byte aligned and both
+ *                      strides multiples of 16 bytes; anything else (any V, any
+ *                      element-aligned pointer) takes a slower element-wise path.
+ *   draft              device, [B, k_max] int32 token ids; slots t >= K_b ignored.
+ *                      May be NULL when k_max == 0.
+ *   draft_len          device, [B] int32 K_b, or NULL meaning K_b = k_max for all b.
+ *   uniforms           device, [B, k_max+1] fp32 in [0,1): column t < K_b drives
+ *                      acceptance test t, column k_max drives the sampled token.
+ *   params             host.
+ *   accepted_len       device, [B] out: n_b in [0, K_b].
+ *   next_token         device, [B] out: the correction token (n_b < K_b) or the
+ *                      bonus token (n_b == K_b).
+ *   next_token_logprob device, [B] out, or NULL: log Softmax(h_rec/T)[next_token].
+ *   recovery_logprobs  device, [B, V] fp32 out, or NULL: log Softmax(h_rec/T) at row n_b.
+ *   draft_logprobs     device, [B, k_max, 2] fp32 out, or NULL:
+ *                      (log P_LLM(y_t), log P_SLM^-(y_t)) for every t < K_b
+ *                      (also past the first rejection); 0 in padded slots.
+ *   workspace          device scratch, 256-byte aligned, at least
+ *                      specsteer_workspace_bytes(params) bytes; contents need no
+ *                      initialisation and are garbage afterwards.  Calls that
+ *                      may overlap in time need distinct workspaces.
+ *   stream             a hipStream_t passed as void*; NULL is the default stream.
+ *
+ * Errors.  Argument errors are detected on the host before anything is
+ * enqueued and leave every output untouched.  Data errors that only the GPU
+ * can see -- draft_len[b] outside [0, k_max], or draft[b][t] outside [0, V)
+ * for some t < K_b -- mark that sequence alone: accepted_len[b] =
+ * next_token[b] = -1, next_token_logprob[b] and its draft_logprobs are NaN, its
+ * recovery_logprobs row is left unwritten; no out-of-range address is ever
+ * formed.  Logits on rows that are read must be finite (behaviour with NaN or
+ * infinities there is unspecified but never faults).
+ */
+ss_status specsteer_verify_block(const void *G, const void *S_ctx, const void *S_noctx,
+                                 const int32_t *draft, const int32_t *draft_len,
+                                 const float *uniforms, const ss_params *params,
+                                 int32_t *accepted_len, int32_t *next_token,
+                                 float *next_token_logprob, float *recovery_logprobs,
+                                 float *draft_logprobs, void *workspace, size_t workspace_bytes,
+                                 void *stream);
+
+/* Static, human-readable name of an ss_status value. */
+const char *specsteer_status_string(int status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int specsteer_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECSTEER_H */

@@ -1,0 +1,143 @@
+"""ctypes binding of the C-ABI library: argument marshalling only.
+
+Every step of the block runs inside ``libspecsteer.so`` (hand-written HIP for
+gfx950); PyTorch supplies device memory and the stream.  There is no CPU or
+PyTorch fallback: if the library cannot be loaded or a call fails, this raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch  # imported before the library so both share one HIP runtime
+
+from . import build as _build
+
+SS_F32, SS_BF16 = 0, 1
+_STATUS_OK = 0
+
+
+class SSParams(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32),
+        ("k_max", ctypes.c_int32),
+        ("vocab", ctypes.c_int32),
+        ("dtype", ctypes.c_int32),
+        ("stride_b", ctypes.c_int64),
+        ("stride_t", ctypes.c_int64),
+        ("lambda_", ctypes.c_float),
+        ("beta", ctypes.c_float),
+        ("temperature", ctypes.c_float),
+        ("flags", ctypes.c_uint32),
+    ]
+
+
+class SpecSteerError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"specsteer status {status}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def library() -> ctypes.CDLL:
+    """Load libspecsteer.so from the package directory (building it only if absent)."""
+    global _lib
+    if _lib is None:
+        path = _build.LIBRARY
+        if not os.path.exists(path):
+            _build.build()
+        lib = ctypes.CDLL(path)
+        lib.specsteer_workspace_bytes.restype = ctypes.c_size_t
+        lib.specsteer_workspace_bytes.argtypes = [ctypes.POINTER(SSParams)]
+        lib.specsteer_verify_block.restype = ctypes.c_int
+        lib.specsteer_verify_block.argtypes = (
+            [ctypes.c_void_p] * 6 + [ctypes.POINTER(SSParams)] + [ctypes.c_void_p] * 6
+            + [ctypes.c_size_t, ctypes.c_void_p])
+        lib.specsteer_status_string.restype = ctypes.c_char_p
+        lib.specsteer_status_string.argtypes = [ctypes.c_int]
+        lib.specsteer_version.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return library().specsteer_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(library().specsteer_version())
+
+
+def make_params(batch: int, k_max: int, vocab: int, dtype: torch.dtype, *, lam: float, beta: float,
+                temperature: float, stride_b: int = 0, stride_t: int = 0, flags: int = 0) -> SSParams:
+    code = {torch.float32: SS_F32, torch.bfloat16: SS_BF16}.get(dtype)
+    if code is None:
+        raise TypeError(f"logits must be float32 or bfloat16, got {dtype}")
+    return SSParams(batch, k_max, vocab, code, stride_b, stride_t, lam, beta, temperature, flags)
+
+
+def workspace_bytes(params: SSParams) -> int:
+    return int(library().specsteer_workspace_bytes(ctypes.byref(params)))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def verify_block_raw(G, S_ctx, S_noctx, draft, draft_len, uniforms, params: SSParams, accepted_len,
+                     next_token, next_token_logprob, recovery_logprobs, draft_logprobs, workspace,
+                     stream: Optional[int] = None) -> None:
+    """Thin call: every tensor is passed by its device pointer, nothing is checked or copied here."""
+    if stream is None:
+        stream = torch.cuda.current_stream(G.device).cuda_stream
+    rc = library().specsteer_verify_block(
+        _ptr(G), _ptr(S_ctx), _ptr(S_noctx), _ptr(draft), _ptr(draft_len), _ptr(uniforms),
+        ctypes.byref(params), _ptr(accepted_len), _ptr(next_token), _ptr(next_token_logprob),
+        _ptr(recovery_logprobs), _ptr(draft_logprobs), _ptr(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(),
+        ctypes.c_void_p(stream))
+    if rc != _STATUS_OK:
+        raise SpecSteerError(rc, status_string(rc))
+
+
+def verify_block(G: torch.Tensor, S_ctx: torch.Tensor, S_noctx: torch.Tensor, draft: torch.Tensor,
+                 uniforms: torch.Tensor, *, lam: float = 0.5, beta: float = 1.0, temperature: float = 1.0,
+                 draft_len: Optional[torch.Tensor] = None, want_recovery_logprobs: bool = False,
+                 want_draft_logprobs: bool = False, workspace: Optional[torch.Tensor] = None) -> dict:
+    """specsteer_verify_block on device tensors G/S_ctx/S_noctx [B, k_max+1, V] (vocab stride 1),
+    draft [B, k_max] int32, uniforms [B, k_max+1] float32.  Allocates the outputs (and a workspace
+    unless one is given) with torch and returns them in a dict; runs on torch's current stream."""
+    if not G.is_cuda:
+        raise ValueError("specsteer_verify_block needs device tensors; there is no CPU path")
+    if not (G.shape == S_ctx.shape == S_noctx.shape) or G.dim() != 3:
+        raise ValueError("logit tensors must share a [B, k_max+1, V] shape")
+    if not (G.dtype == S_ctx.dtype == S_noctx.dtype):
+        raise ValueError("logit tensors must share a dtype")
+    if not (G.stride() == S_ctx.stride() == S_noctx.stride()) or G.stride(2) != 1:
+        raise ValueError("logit tensors must share strides, with the vocabulary contiguous")
+    B, k1, V = G.shape
+    k_max = k1 - 1
+    dev = G.device
+    draft = draft.to(device=dev, dtype=torch.int32).contiguous()
+    uniforms = uniforms.to(device=dev, dtype=torch.float32).contiguous()
+    if draft_len is not None:
+        draft_len = draft_len.to(device=dev, dtype=torch.int32).contiguous()
+    params = make_params(B, k_max, V, G.dtype, lam=lam, beta=beta, temperature=temperature,
+                         stride_b=G.stride(0) if B > 1 else 0, stride_t=G.stride(1) if k1 > 1 else 0)
+    need = workspace_bytes(params)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    out = {
+        "accepted_len": torch.empty(B, dtype=torch.int32, device=dev),
+        "next_token": torch.empty(B, dtype=torch.int32, device=dev),
+        "next_token_logprob": torch.empty(B, dtype=torch.float32, device=dev),
+        "recovery_logprobs": torch.empty(B, V, dtype=torch.float32, device=dev) if want_recovery_logprobs else None,
+        "draft_logprobs": torch.empty(B, k_max, 2, dtype=torch.float32, device=dev) if want_draft_logprobs else None,
+    }
+    verify_block_raw(G, S_ctx, S_noctx, draft if k_max > 0 else None, draft_len, uniforms, params,
+                     out["accepted_len"], out["next_token"], out["next_token_logprob"],
+                     out["recovery_logprobs"], out["draft_logprobs"], workspace)
+    return out

@@ -1,0 +1,796 @@
+// SpecSteer verify-and-recover block for MI355X (gfx950): HIP kernels and the C ABI.
+//
+// What is computed (Algorithm 1 phases 2-3, Eq. 7, Eq. 8) is stated in
+// include/specsteer.h.  How it is computed here:
+//
+//   prep_rows      (ragged batches only) exclusive scan of the draft lengths, so the
+//                  valid (sequence, position) rows form one dense list.
+//   row_lse        the dominant, HBM-bound pass.  Every valid row of G and S_noctx is
+//                  cut into slices; one 64-lane wavefront streams one slice with
+//                  16-byte loads and keeps a per-lane running (E, s) with
+//                  sum_v 2^(h_v*c - E) = s,  c = log2(e)/T,  E an integer >= max(h*c).
+//                  An integer reference makes every rescale an exact ldexp and costs
+//                  no extra exponential: one v_exp_f32 per logit.  Waves never
+//                  synchronise with each other (no LDS, no barrier); a persistent grid
+//                  strides over the slice list.
+//   accept_recover one workgroup per sequence.  Wave 0 combines the slice partials in
+//                  double, gathers the two draft-token logits per position, applies the
+//                  ratio test and finds the first rejection with a wave ballot.  All
+//                  waves then stream the three logit rows of the rejected (or bonus)
+//                  position once, forming h_rec in double, and record one (E, s) mass per
+//                  2048-logit chunk in LDS.  A double-precision scan over the chunk
+//                  masses locates the chunk holding u*Z; only that chunk is read again
+//                  to pick the token.  The full log-prob row is a second sweep, taken
+//                  only when the caller asks for it.
+//
+// Precision: logits are widened exactly; sums of exponentials are accumulated in
+// fp32 (one rounding per term, pairwise across lanes), every per-row scalar
+// (log-sum-exp combine, log-probs, alpha, CDF walk across chunks) is double.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+
+#include "specsteer.h"
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kLseThreads = 256;            // 4 independent waves per workgroup
+constexpr int kLseUnroll = 4;               // 16-byte loads in flight per lane
+constexpr int kMinSliceVecs = kWave * kLseUnroll;  // smallest slice: one unrolled group
+constexpr int kMaxSliceVecs = 2048;         // 32 KiB of logits per slice
+constexpr int kMaxSlices = 64;
+constexpr int kChunkSteps = 4;              // recovery chunk = 4 wave-steps (2048 bf16 logits)
+constexpr int kEInit = -(1 << 29);          // "no logit seen yet" exponent reference
+constexpr float kEClamp = 5.0e8f;           // keeps (int)ceil(h*c) inside int32 for any finite h
+constexpr double kLn2 = 0.693147180559945309417232121458;
+constexpr double kLog2e = 1.442695040888963407359924681002;
+
+struct Partial {
+    int E;    // integer exponent reference of this slice
+    float s;  // sum over the slice of 2^(h*c - E)
+};
+
+// ------------------------------------------------------------------ wave primitives
+
+// Cross-lane moves inside a row of 16 lanes use DPP; all four patterns below read a valid
+// lane for every destination lane, so neither `old` nor bound_ctrl matters.
+template <int CTRL>
+__device__ __forceinline__ int dpp_mov(int v) {
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xF, 0xF, false);
+}
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i inside each 8
+constexpr int kDppMirror = 0x140;     // lane i <-> 15-i inside each 16
+
+__device__ __forceinline__ int wave_max_i32(int v) {
+    v = max(v, dpp_mov<kDppXor1>(v));
+    v = max(v, dpp_mov<kDppXor2>(v));
+    v = max(v, dpp_mov<kDppHalfMirror>(v));
+    v = max(v, dpp_mov<kDppMirror>(v));
+    // every lane of a 16-lane row now holds its row's maximum
+    const int a = __builtin_amdgcn_readlane(v, 0), b = __builtin_amdgcn_readlane(v, 16);
+    const int c = __builtin_amdgcn_readlane(v, 32), d = __builtin_amdgcn_readlane(v, 48);
+    return max(max(a, b), max(c, d));
+}
+
+__device__ __forceinline__ float wave_sum_f32(float x) {
+    x += __int_as_float(dpp_mov<kDppXor1>(__float_as_int(x)));
+    x += __int_as_float(dpp_mov<kDppXor2>(__float_as_int(x)));
+    x += __int_as_float(dpp_mov<kDppHalfMirror>(__float_as_int(x)));
+    x += __int_as_float(dpp_mov<kDppMirror>(__float_as_int(x)));
+    const int v = __float_as_int(x);
+    const float a = __int_as_float(__builtin_amdgcn_readlane(v, 0));
+    const float b = __int_as_float(__builtin_amdgcn_readlane(v, 16));
+    const float c = __int_as_float(__builtin_amdgcn_readlane(v, 32));
+    const float d = __int_as_float(__builtin_amdgcn_readlane(v, 48));
+    return (a + b) + (c + d);
+}
+
+// Inclusive prefix sum over the 64 lanes (rare, per-sequence scalar work: plain shuffles).
+__device__ __forceinline__ double wave_incl_scan_f64(double x, int lane) {
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const double y = __shfl_up(x, d, kWave);
+        if (lane >= d) x += y;
+    }
+    return x;
+}
+
+__device__ __forceinline__ int first_lane(unsigned long long mask) { return __ffsll((long long)mask) - 1; }
+
+// ------------------------------------------------------------------ logit loads
+
+template <int DT, int VEC> struct RawT;
+template <> struct RawT<SS_BF16, 8> { using type = uint4; };
+template <> struct RawT<SS_F32, 4> { using type = float4; };
+template <> struct RawT<SS_BF16, 1> { using type = unsigned short; };
+template <> struct RawT<SS_F32, 1> { using type = float; };
+
+template <int DT, int VEC>
+__device__ __forceinline__ typename RawT<DT, VEC>::type ld_raw(const void* row, long vec) {
+    using R = typename RawT<DT, VEC>::type;
+    return reinterpret_cast<const R*>(row)[vec];
+}
+
+__device__ __forceinline__ float bf16_lo(unsigned w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(unsigned w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+__device__ __forceinline__ void unpack(const uint4& r, float (&h)[8]) {
+    h[0] = bf16_lo(r.x); h[1] = bf16_hi(r.x);
+    h[2] = bf16_lo(r.y); h[3] = bf16_hi(r.y);
+    h[4] = bf16_lo(r.z); h[5] = bf16_hi(r.z);
+    h[6] = bf16_lo(r.w); h[7] = bf16_hi(r.w);
+}
+__device__ __forceinline__ void unpack(const float4& r, float (&h)[4]) {
+    h[0] = r.x; h[1] = r.y; h[2] = r.z; h[3] = r.w;
+}
+__device__ __forceinline__ void unpack(unsigned short r, float (&h)[1]) { h[0] = __uint_as_float((unsigned)r << 16); }
+__device__ __forceinline__ void unpack(float r, float (&h)[1]) { h[0] = r; }
+
+template <int DT>
+__device__ __forceinline__ float ld_elem(const void* row, long e) {
+    if (DT == SS_BF16) return __uint_as_float((unsigned)reinterpret_cast<const unsigned short*>(row)[e] << 16);
+    return reinterpret_cast<const float*>(row)[e];
+}
+
+template <int DT>
+__device__ __forceinline__ const void* row_ptr(const void* base, long elem_off) {
+    return reinterpret_cast<const char*>(base) + elem_off * (DT == SS_BF16 ? 2 : 4);
+}
+
+// ------------------------------------------------------------------ online sum of exponentials
+
+struct Acc {
+    int E;
+    float s;
+};
+
+__device__ __forceinline__ int exp_ref(float scaled_max) {
+    return (int)ceilf(fminf(fmaxf(scaled_max, -kEClamp), kEClamp));
+}
+
+// fp32 path of the row pass: term = 2^(h*c - E) with c = c_hi + c_lo carried as two floats,
+// so the rounding of c does not scale with |h| (it would cost |h/T| * 2^-24 in the log-sum).
+template <int N>
+__device__ __forceinline__ void acc_add_f32(Acc& a, const float (&h)[N], float c_hi, float c_lo) {
+    float m = h[0];
+#pragma unroll
+    for (int i = 1; i < N; ++i) m = fmaxf(m, h[i]);
+    const int En = max(a.E, exp_ref(m * c_hi));
+    a.s = ldexpf(a.s, a.E - En);
+    a.E = En;
+    const float nE = -(float)En;
+    float t0 = 0.f, t1 = 0.f;
+#pragma unroll
+    for (int i = 0; i < N; i += 2) {
+        t0 += __builtin_amdgcn_exp2f(fmaf(h[i], c_lo, fmaf(h[i], c_hi, nE)));
+        if (i + 1 < N) t1 += __builtin_amdgcn_exp2f(fmaf(h[i + 1], c_lo, fmaf(h[i + 1], c_hi, nE)));
+    }
+    a.s += t0 + t1;
+}
+
+// recovery logit in the base-2 exponent domain: y = (G + beta*(S_ctx - S_noctx)) * log2(e)/T, in double.
+__device__ __forceinline__ double rec_y(float g, float sp, float sm, double c, double bc) {
+    return fma((double)g, c, ((double)sp - (double)sm) * bc);
+}
+
+template <int N>
+__device__ __forceinline__ void acc_add_f64(Acc& a, const double (&y)[N]) {
+    double m = y[0];
+#pragma unroll
+    for (int i = 1; i < N; ++i) m = fmax(m, y[i]);
+    const int En = max(a.E, exp_ref((float)m));
+    a.s = ldexpf(a.s, a.E - En);
+    a.E = En;
+    const double dE = (double)En;
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < N; ++i) t += __builtin_amdgcn_exp2f((float)(y[i] - dE));
+    a.s += t;
+}
+
+__device__ __forceinline__ Partial wave_combine(Acc a) {
+    const int Em = wave_max_i32(a.E);
+    const float S = wave_sum_f32(ldexpf(a.s, a.E - Em));
+    return Partial{Em, S};
+}
+
+// ------------------------------------------------------------------ kernel: ragged row list
+
+// row_off[b] = number of valid (sequence, position) rows before sequence b; row_off[B] = total.
+// A length outside [0, k_max] contributes no rows (the sequence is flagged later).
+__global__ __launch_bounds__(1024) void prep_rows_kernel(const int32_t* __restrict__ draft_len, int B, int kmax,
+                                                         int32_t* __restrict__ row_off) {
+    __shared__ int wave_tot[16];
+    __shared__ int carry;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) carry = 0;
+    __syncthreads();
+    for (int b0 = 0; b0 < B; b0 += 1024) {
+        const int b = b0 + tid;
+        int k = 0;
+        if (b < B) {
+            k = draft_len[b];
+            if (k < 0 || k > kmax) k = 0;
+        }
+        int incl = k;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int y = __shfl_up(incl, d, kWave);
+            if (lane >= d) incl += y;
+        }
+        if (lane == 63) wave_tot[wave] = incl;
+        __syncthreads();
+        int before = carry;
+        for (int w = 0; w < wave; ++w) before += wave_tot[w];
+        if (b < B) row_off[b] = before + incl - k;
+        __syncthreads();
+        if (tid == 1023) carry = before + incl;
+        __syncthreads();
+    }
+    if (tid == 0) row_off[B] = carry;
+}
+
+// ------------------------------------------------------------------ kernel: row log-sum-exp partials
+
+struct LseArgs {
+    const void* G;
+    const void* Sm;
+    const int32_t* row_off;  // NULL => every sequence has k_max rows
+    Partial* partial;        // [rows][2][NS]
+    long sb, st;             // element strides
+    int B, kmax, V, NS;
+    int slice_vecs;          // vectors (of the fast path's width) per slice
+    float c_hi, c_lo;
+};
+
+template <int DT, int VEC, int VECFAST>
+__global__ __launch_bounds__(kLseThreads) void row_lse_kernel(const LseArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int wave_global = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (kLseThreads / kWave) + (threadIdx.x >> 6)));
+    const int waves_total = gridDim.x * (kLseThreads / kWave);
+    const int R = a.row_off ? a.row_off[a.B] : a.B * a.kmax;
+    const long items = (long)R * 2 * a.NS;
+    // a slice is slice_vecs vectors of the fast width; the element-wise path covers the same logits
+    const long slice_units = (long)a.slice_vecs * (VECFAST / VEC);
+    const long nvec = a.V / VEC;
+    const int tailc = a.V - (int)(nvec * VEC);
+
+    for (long item = wave_global; item < items; item += waves_total) {
+        const int k = (int)(item % a.NS);
+        const long rx = item / a.NS;
+        const int x = (int)(rx & 1);
+        const int r = (int)(rx >> 1);
+        int b, t;
+        if (a.row_off) {
+            int lo = 0, hi = a.B;  // largest b with row_off[b] <= r; row_off[B] = R > r
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (a.row_off[mid] <= r) lo = mid; else hi = mid;
+            }
+            b = lo;
+            t = r - a.row_off[b];
+        } else {
+            b = r / a.kmax;
+            t = r - b * a.kmax;
+        }
+        const void* row = row_ptr<DT>(x ? a.Sm : a.G, (long)b * a.sb + (long)t * a.st);
+        const long v0 = (long)k * slice_units;
+        const long v1 = min(nvec, v0 + slice_units);
+
+        Acc acc{kEInit, 0.f};
+        long v = v0 + lane;
+        for (; v + (long)kWave * (kLseUnroll - 1) < v1; v += (long)kWave * kLseUnroll) {
+            typename RawT<DT, VEC>::type raw[kLseUnroll];
+#pragma unroll
+            for (int j = 0; j < kLseUnroll; ++j) raw[j] = ld_raw<DT, VEC>(row, v + (long)kWave * j);
+            float h[kLseUnroll * VEC];
+#pragma unroll
+            for (int j = 0; j < kLseUnroll; ++j) {
+                float hj[VEC];
+                unpack(raw[j], hj);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) h[j * VEC + i] = hj[i];
+            }
+            acc_add_f32<kLseUnroll * VEC>(acc, h, a.c_hi, a.c_lo);
+        }
+        for (; v < v1; v += kWave) {
+            float hj[VEC];
+            unpack(ld_raw<DT, VEC>(row, v), hj);
+            acc_add_f32<VEC>(acc, hj, a.c_hi, a.c_lo);
+        }
+        if (k == a.NS - 1 && lane < tailc) {  // logits past the last full vector
+            float hj[1] = {ld_elem<DT>(row, nvec * VEC + lane)};
+            acc_add_f32<1>(acc, hj, a.c_hi, a.c_lo);
+        }
+        const Partial p = wave_combine(acc);
+        if (lane == 0) a.partial[item] = p;
+    }
+}
+
+// ------------------------------------------------------------------ kernel: accept + recover
+
+struct RecArgs {
+    const void* G;
+    const void* Sp;
+    const void* Sm;
+    const int32_t* draft;
+    const int32_t* draft_len;
+    const float* uniforms;
+    const int32_t* row_off;
+    const Partial* partial;
+    int32_t* accepted_len;
+    int32_t* next_token;
+    float* next_token_logprob;
+    float* recovery_logprobs;
+    float* draft_logprobs;
+    long sb, st;
+    int B, kmax, V, NS;
+    double c;        // log2(e) / T
+    double bc;       // beta * log2(e) / T
+    double ln_lambda;
+};
+
+// log2 of sum_v 2^(h_v * c) for one row, from its slice partials.
+__device__ __forceinline__ double combine_partials(const Partial* p, int NS) {
+    int Em = p[0].E;
+    for (int k = 1; k < NS; ++k) Em = max(Em, p[k].E);
+    double S = 0.0;
+    for (int k = 0; k < NS; ++k) S += ldexp((double)p[k].s, p[k].E - Em);
+    return (double)Em + log2(S);
+}
+
+// The logits one lane owns in step j of chunk c, as recovery exponents y.  Regular chunks hold
+// kChunkSteps wave-steps of full vectors; the pseudo-chunk c == nch holds the < VEC logits
+// past the last full vector, one per lane.  Returns how many entries of y are valid and the
+// vocabulary index of the first.
+template <int DT, int VEC>
+__device__ __forceinline__ int chunk_lane_y(const void* g, const void* sp, const void* sm, long nvec, int tailc,
+                                            long nch, long c, int j, int lane, double cc, double bc,
+                                            double (&y)[VEC], long& first) {
+    if (c < nch) {
+        const long v = c * (long)(kWave * kChunkSteps) + (long)j * kWave + lane;
+        first = v * VEC;
+        if (v >= nvec) return 0;
+        float hg[VEC], hp[VEC], hm[VEC];
+        unpack(ld_raw<DT, VEC>(g, v), hg);
+        unpack(ld_raw<DT, VEC>(sp, v), hp);
+        unpack(ld_raw<DT, VEC>(sm, v), hm);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) y[i] = rec_y(hg[i], hp[i], hm[i], cc, bc);
+        return VEC;
+    }
+    first = nvec * VEC + lane;
+    if (j > 0 || lane >= tailc) return 0;
+    y[0] = rec_y(ld_elem<DT>(g, first), ld_elem<DT>(sp, first), ld_elem<DT>(sm, first), cc, bc);
+    return 1;
+}
+
+template <int DT, int VEC>
+__global__ __launch_bounds__(1024) void accept_recover_kernel(const RecArgs a) {
+    extern __shared__ int smem[];
+    __shared__ int sh_n, sh_bad;
+    __shared__ double sh_log2Z;
+
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int NT = blockDim.x, NW = NT >> 6;
+    const int kmax = a.kmax, V = a.V;
+
+    const int K = a.draft_len ? a.draft_len[b] : kmax;
+    const bool bad_len = (K < 0 || K > kmax);
+
+    // ---- phase 2: ratio test on every drafted position, first rejection by wave ballot
+    if (wave == 0) {
+        int first_rej = bad_len ? 0 : K;
+        bool any_bad = bad_len;
+        const long r0 = a.row_off ? a.row_off[b] : (long)b * kmax;
+        for (int t0 = 0; !bad_len && t0 < K; t0 += kWave) {
+            const int t = t0 + lane;
+            bool rej = false, oob = false;
+            if (t < K) {
+                const int y = a.draft[(long)b * kmax + t];
+                if (y < 0 || y >= V) {
+                    oob = true;
+                } else {
+                    const Partial* p = a.partial + (r0 + t) * 2 * a.NS;
+                    const double LG = combine_partials(p, a.NS);
+                    const double LS = combine_partials(p + a.NS, a.NS);
+                    const long off = (long)b * a.sb + (long)t * a.st;
+                    const double hG = (double)ld_elem<DT>(row_ptr<DT>(a.G, off), y);
+                    const double hS = (double)ld_elem<DT>(row_ptr<DT>(a.Sm, off), y);
+                    const double lpG = kLn2 * (hG * a.c - LG);  // log P_LLM(y_t)
+                    const double lpS = kLn2 * (hS * a.c - LS);  // log P_SLM^-(y_t)
+                    const double alpha = fmin(1.0, exp(lpG - lpS - a.ln_lambda));  // Eq. 7
+                    rej = !((double)a.uniforms[(long)b * (kmax + 1) + t] <= alpha);
+                    if (a.draft_logprobs) {
+                        a.draft_logprobs[((long)b * kmax + t) * 2 + 0] = (float)lpG;
+                        a.draft_logprobs[((long)b * kmax + t) * 2 + 1] = (float)lpS;
+                    }
+                }
+            }
+            any_bad = any_bad || (__ballot(oob) != 0ull);
+            const unsigned long long rmask = __ballot(rej);
+            if (rmask && first_rej == K) first_rej = t0 + first_lane(rmask);
+        }
+        if (lane == 0) {
+            sh_n = first_rej;
+            sh_bad = any_bad ? 1 : 0;
+        }
+    }
+    __syncthreads();
+    const int n = sh_n;
+    const bool bad = sh_bad != 0;
+
+    if (a.draft_logprobs) {  // padded slots read 0, a flagged sequence reads NaN throughout
+        const int from = bad ? 0 : K;
+        const float fill = bad ? __int_as_float(0x7FC00000) : 0.f;
+        for (int i = from * 2 + tid; i < kmax * 2; i += NT) a.draft_logprobs[(long)b * kmax * 2 + i] = fill;
+    }
+    if (bad) {
+        if (tid == 0) {
+            a.accepted_len[b] = -1;
+            a.next_token[b] = -1;
+            if (a.next_token_logprob) a.next_token_logprob[b] = __int_as_float(0x7FC00000);
+        }
+        return;
+    }
+
+    // ---- phase 3: one sweep over the three rows at position n, one (E, s) mass per chunk
+    const long off = (long)b * a.sb + (long)n * a.st;
+    const void* g = row_ptr<DT>(a.G, off);
+    const void* sp = row_ptr<DT>(a.Sp, off);
+    const void* sm = row_ptr<DT>(a.Sm, off);
+    const long nvec = V / VEC;
+    const int tailc = V - (int)(nvec * VEC);
+    const long nch = (nvec + kWave * kChunkSteps - 1) / (kWave * kChunkSteps);
+    const int NC = (int)nch + (tailc ? 1 : 0);
+    int* chE = smem;
+    float* chS = reinterpret_cast<float*>(smem + NC);
+
+    for (long c = wave; c < NC; c += NW) {
+        Acc acc{kEInit, 0.f};
+        if (c < nch) {
+            const long vbase = c * (long)(kWave * kChunkSteps) + lane;
+            typename RawT<DT, VEC>::type rg[kChunkSteps], rp[kChunkSteps], rm[kChunkSteps];
+#pragma unroll
+            for (int j = 0; j < kChunkSteps; ++j) {
+                const long v = vbase + (long)j * kWave;
+                if (v < nvec) {
+                    rg[j] = ld_raw<DT, VEC>(g, v);
+                    rp[j] = ld_raw<DT, VEC>(sp, v);
+                    rm[j] = ld_raw<DT, VEC>(sm, v);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < kChunkSteps; ++j) {
+                const long v = vbase + (long)j * kWave;
+                if (v < nvec) {
+                    float hg[VEC], hp[VEC], hm[VEC];
+                    unpack(rg[j], hg);
+                    unpack(rp[j], hp);
+                    unpack(rm[j], hm);
+                    double y[VEC];
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) y[i] = rec_y(hg[i], hp[i], hm[i], a.c, a.bc);
+                    acc_add_f64<VEC>(acc, y);
+                }
+            }
+        } else if (lane < tailc) {
+            const long e = nvec * VEC + lane;
+            double y[1] = {rec_y(ld_elem<DT>(g, e), ld_elem<DT>(sp, e), ld_elem<DT>(sm, e), a.c, a.bc)};
+            acc_add_f64<1>(acc, y);
+        }
+        const Partial p = wave_combine(acc);
+        if (lane == 0) {
+            chE[c] = p.E;
+            chS[c] = p.s;
+        }
+    }
+    __syncthreads();
+
+    // ---- locate u*Z among the chunk masses (double), then walk that one chunk again
+    if (wave == 0) {
+        int Em = kEInit;
+        for (int c = lane; c < NC; c += kWave) Em = max(Em, chE[c]);
+        const int Estar = wave_max_i32(Em);
+        const int per = (NC + kWave - 1) / kWave;
+        const int lo = min(lane * per, NC), hi = min(lo + per, NC);
+        double lsum = 0.0;
+        for (int c = lo; c < hi; ++c) lsum += ldexp((double)chS[c], chE[c] - Estar);
+        const double incl = wave_incl_scan_f64(lsum, lane);
+        const double total = __shfl(incl, 63, kWave);
+        double excl = __shfl_up(incl, 1, kWave);
+        if (lane == 0) excl = 0.0;
+        const double us = (double)a.uniforms[(long)b * (kmax + 1) + kmax];
+        const double target = us * total;
+
+        int cfound = -1, clast = -1;
+        double cbase = 0.0, cum = excl;
+        for (int c = lo; c < hi; ++c) {
+            const double m = ldexp((double)chS[c], chE[c] - Estar);
+            if (m > 0.0) clast = c;
+            const double cum2 = cum + m;
+            if (cfound < 0 && cum2 > target) {
+                cfound = c;
+                cbase = cum;
+            }
+            cum = cum2;
+        }
+        const unsigned long long fmask = __ballot(cfound >= 0);
+        int cstar;
+        double base;
+        bool take_last = false;  // the uniform is not below the total mass (u >= 1 or not a number)
+        if (fmask) {
+            const int L = first_lane(fmask);
+            cstar = __shfl(cfound, L, kWave);
+            base = __shfl(cbase, L, kWave);
+        } else {
+            cstar = max(wave_max_i32(clast), 0);
+            base = 0.0;
+            take_last = true;
+        }
+
+        const double dE = (double)Estar;
+        const int nsteps = (cstar < nch) ? kChunkSteps : 1;
+        double run = base;
+        long tok = -1, lastpos = -1;
+        double ytok = 0.0, ylast = 0.0;
+        for (int j = 0; j < nsteps && tok < 0; ++j) {
+            double y[VEC];
+            long first;
+            const int cnt = chunk_lane_y<DT, VEC>(g, sp, sm, nvec, tailc, nch, cstar, j, lane, a.c, a.bc, y, first);
+            double p[VEC];
+            double ls = 0.0;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                p[i] = (i < cnt) ? (double)__builtin_amdgcn_exp2f((float)(y[i] - dE)) : 0.0;
+                ls += p[i];
+                if (i < cnt && p[i] > 0.0) {
+                    lastpos = first + i;
+                    ylast = y[i];
+                }
+            }
+            const double inc = wave_incl_scan_f64(ls, lane);
+            double before = __shfl_up(inc, 1, kWave);
+            if (lane == 0) before = 0.0;
+            before += run;
+            long mytok = -1;
+            double myy = 0.0, cw = before;
+            if (!take_last) {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) {
+                    cw += p[i];
+                    if (mytok < 0 && i < cnt && cw > target) {
+                        mytok = first + i;
+                        myy = y[i];
+                    }
+                }
+            }
+            const unsigned long long hmask = __ballot(mytok >= 0);
+            if (hmask) {
+                const int L = first_lane(hmask);
+                tok = __shfl(mytok, L, kWave);
+                ytok = __shfl(myy, L, kWave);
+            }
+            run += __shfl(inc, 63, kWave);
+        }
+        if (tok < 0) {
+            // rounding between the chunk table and the re-read (or take_last): the last logit of
+            // the chunk that still carries probability
+            long best = lastpos;
+#pragma unroll
+            for (int d = 1; d < kWave; d <<= 1) best = max(best, __shfl_xor(best, d, kWave));
+            const unsigned long long omask = __ballot(lastpos == best && best >= 0);
+            if (omask) {
+                tok = best;
+                ytok = __shfl(ylast, first_lane(omask), kWave);
+            } else {  // unreachable for finite logits; keep the index valid
+                tok = min((long)cstar * (kWave * kChunkSteps * VEC), (long)V - 1);
+                ytok = dE;
+            }
+        }
+        const double log2Z = dE + log2(total);
+        if (lane == 0) {
+            sh_log2Z = log2Z;
+            a.accepted_len[b] = n;
+            a.next_token[b] = (int32_t)tok;
+            if (a.next_token_logprob) a.next_token_logprob[b] = (float)(kLn2 * (ytok - log2Z));
+        }
+    }
+
+    // ---- optional: the whole log Softmax(h_rec / T) row
+    if (a.recovery_logprobs) {
+        __syncthreads();
+        const double log2Z = sh_log2Z;
+        float* out = a.recovery_logprobs + (long)b * V;
+        for (long v = tid; v < nvec; v += NT) {
+            float hg[VEC], hp[VEC], hm[VEC];
+            unpack(ld_raw<DT, VEC>(g, v), hg);
+            unpack(ld_raw<DT, VEC>(sp, v), hp);
+            unpack(ld_raw<DT, VEC>(sm, v), hm);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i)
+                out[v * VEC + i] = (float)(kLn2 * (rec_y(hg[i], hp[i], hm[i], a.c, a.bc) - log2Z));
+        }
+        if (tid < tailc) {
+            const long e = nvec * VEC + tid;
+            out[e] = (float)(kLn2 * (rec_y(ld_elem<DT>(g, e), ld_elem<DT>(sp, e), ld_elem<DT>(sm, e), a.c, a.bc) - log2Z));
+        }
+    }
+}
+
+// ------------------------------------------------------------------ host side
+
+struct Plan {
+    int vecfast;     // logits per 16-byte vector
+    int NS;          // slices per row
+    int slice_vecs;  // fast-width vectors per slice
+    size_t off_partial;
+    size_t bytes;
+};
+
+bool shape_ok(const ss_params* p) {
+    if (!p) return false;
+    if (p->batch < 0 || p->k_max < 0 || p->k_max > SS_MAX_K) return false;
+    if (p->vocab < 1 || p->vocab > SS_MAX_VOCAB) return false;
+    if (p->dtype != SS_F32 && p->dtype != SS_BF16) return false;
+    if ((long)p->batch * (p->k_max + 1) > (1l << 30)) return false;
+    return true;
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Slices per row: 32 KiB slices for big batches, smaller ones (down to one unrolled group)
+// when there are too few rows to give every resident wave several slices.
+Plan make_plan(const ss_params* p) {
+    Plan pl;
+    pl.vecfast = p->dtype == SS_BF16 ? 8 : 4;
+    const long nvec = (p->vocab + pl.vecfast - 1) / pl.vecfast;
+    const long rows2 = (long)p->batch * p->k_max * 2;
+    long ns_lo = (nvec + kMaxSliceVecs - 1) / kMaxSliceVecs;
+    long ns_hi = (nvec + kMinSliceVecs - 1) / kMinSliceVecs;
+    long want = rows2 > 0 ? (32768 + rows2 - 1) / rows2 : 1;
+    long ns = want < ns_lo ? ns_lo : (want > ns_hi ? ns_hi : want);
+    if (ns > kMaxSlices) ns = kMaxSlices;
+    if (ns < 1) ns = 1;
+    long sv = (nvec + ns - 1) / ns;
+    sv = (sv + kMinSliceVecs - 1) / kMinSliceVecs * kMinSliceVecs;
+    ns = (nvec + sv - 1) / sv;
+    if (ns < 1) ns = 1;
+    pl.NS = (int)ns;
+    pl.slice_vecs = (int)sv;
+    pl.off_partial = align_up(((size_t)p->batch + 1) * sizeof(int32_t), 256);
+    pl.bytes = pl.off_partial + align_up((size_t)(rows2 > 0 ? rows2 : 1) * pl.NS * sizeof(Partial), 256);
+    return pl;
+}
+
+int device_cu_count() {
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+template <int DT, int VEC, int VECFAST>
+hipError_t launch_all(const LseArgs& la, const RecArgs& ra, const int32_t* draft_len, int32_t* row_off,
+                      hipStream_t stream) {
+    const int B = ra.B, kmax = ra.kmax, V = ra.V;
+    if (draft_len && kmax > 0)
+        hipLaunchKernelGGL(prep_rows_kernel, dim3(1), dim3(1024), 0, stream, draft_len, B, kmax, row_off);
+    const long items = (long)B * kmax * 2 * la.NS;
+    if (items > 0) {
+        const long per_wg = kLseThreads / kWave;
+        long wgs = (items + per_wg - 1) / per_wg;
+        const long cap = (long)device_cu_count() * 8;
+        if (wgs > cap) wgs = cap;
+        hipLaunchKernelGGL((row_lse_kernel<DT, VEC, VECFAST>), dim3((unsigned)wgs), dim3(kLseThreads), 0, stream, la);
+    }
+    const long nvec = V / VEC;
+    const long nch = (nvec + kWave * kChunkSteps - 1) / (kWave * kChunkSteps);
+    const size_t smem = (size_t)(nch + 1) * 8;
+    // a long row is worth a full 16-wave workgroup; many sequences fill the chip either way
+    const int nt = 1024;
+    hipLaunchKernelGGL((accept_recover_kernel<DT, VEC>), dim3((unsigned)B), dim3(nt), smem, stream, ra);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t specsteer_workspace_bytes(const ss_params* params) {
+    if (!shape_ok(params)) return 0;
+    return make_plan(params).bytes;
+}
+
+ss_status specsteer_verify_block(const void* G, const void* S_ctx, const void* S_noctx, const int32_t* draft,
+                                 const int32_t* draft_len, const float* uniforms, const ss_params* params,
+                                 int32_t* accepted_len, int32_t* next_token, float* next_token_logprob,
+                                 float* recovery_logprobs, float* draft_logprobs, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+    if (!params) return SS_ERR_NULL;
+    if (params->dtype != SS_F32 && params->dtype != SS_BF16) return SS_ERR_DTYPE;
+    if (!shape_ok(params)) return SS_ERR_SHAPE;
+    if (!G || !S_ctx || !S_noctx || !uniforms || !accepted_len || !next_token) return SS_ERR_NULL;
+    if (params->k_max > 0 && !draft) return SS_ERR_NULL;
+    if (!(params->lambda > 0.f) || !std::isfinite(params->lambda)) return SS_ERR_PARAM;
+    if (!(params->temperature > 0.f) || !std::isfinite(params->temperature)) return SS_ERR_PARAM;
+    if (!std::isfinite(params->beta)) return SS_ERR_PARAM;
+    if (params->flags != 0) return SS_ERR_PARAM;
+    const long V = params->vocab;
+    if (params->stride_t < 0 || params->stride_b < 0) return SS_ERR_STRIDE;
+    const long st = params->stride_t ? params->stride_t : V;
+    const long sb = params->stride_b ? params->stride_b : (long)(params->k_max + 1) * st;
+    if (st < V || sb < (long)params->k_max * st + V) return SS_ERR_STRIDE;
+    const Plan pl = make_plan(params);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 || workspace_bytes < pl.bytes)
+        return SS_ERR_WORKSPACE;
+    if (params->batch == 0) return SS_OK;
+
+    const int esz = params->dtype == SS_BF16 ? 2 : 4;
+    const bool fast = ((reinterpret_cast<uintptr_t>(G) | reinterpret_cast<uintptr_t>(S_ctx) |
+                        reinterpret_cast<uintptr_t>(S_noctx)) & 15) == 0 &&
+                      (st * esz) % 16 == 0 && (sb * esz) % 16 == 0;
+
+    char* ws = static_cast<char*>(workspace);
+    int32_t* row_off = reinterpret_cast<int32_t*>(ws);
+    Partial* partial = reinterpret_cast<Partial*>(ws + pl.off_partial);
+    const bool ragged = draft_len != nullptr && params->k_max > 0;
+
+    // c = log2(e)/T as an unevaluated sum of two floats for the fp32 row pass
+    const double T = (double)params->temperature;
+    const double c = kLog2e / T;
+    const float c_hi = (float)c;
+    const float c_lo = (float)(c - (double)c_hi);
+
+    LseArgs la;
+    la.G = G; la.Sm = S_noctx; la.row_off = ragged ? row_off : nullptr; la.partial = partial;
+    la.sb = sb; la.st = st; la.B = params->batch; la.kmax = params->k_max; la.V = params->vocab;
+    la.NS = pl.NS; la.slice_vecs = pl.slice_vecs; la.c_hi = c_hi; la.c_lo = c_lo;
+
+    RecArgs ra;
+    ra.G = G; ra.Sp = S_ctx; ra.Sm = S_noctx; ra.draft = draft; ra.draft_len = draft_len; ra.uniforms = uniforms;
+    ra.row_off = la.row_off; ra.partial = partial; ra.accepted_len = accepted_len; ra.next_token = next_token;
+    ra.next_token_logprob = next_token_logprob; ra.recovery_logprobs = recovery_logprobs;
+    ra.draft_logprobs = draft_logprobs; ra.sb = sb; ra.st = st; ra.B = params->batch; ra.kmax = params->k_max;
+    ra.V = params->vocab; ra.NS = pl.NS; ra.c = c; ra.bc = (double)params->beta * c;
+    ra.ln_lambda = std::log((double)params->lambda);
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t err;
+    if (params->dtype == SS_BF16) {
+        err = fast ? launch_all<SS_BF16, 8, 8>(la, ra, draft_len, row_off, s)
+                   : launch_all<SS_BF16, 1, 8>(la, ra, draft_len, row_off, s);
+    } else {
+        err = fast ? launch_all<SS_F32, 4, 4>(la, ra, draft_len, row_off, s)
+                   : launch_all<SS_F32, 1, 4>(la, ra, draft_len, row_off, s);
+    }
+    return err == hipSuccess ? SS_OK : SS_ERR_DEVICE;
+}
+
+const char* specsteer_status_string(int status) {
+    switch (status) {
+        case SS_OK: return "ok";
+        case SS_ERR_NULL: return "a required pointer is NULL";
+        case SS_ERR_SHAPE: return "batch, k_max or vocab out of range";
+        case SS_ERR_DTYPE: return "unknown logits dtype";
+        case SS_ERR_PARAM: return "lambda, beta, temperature or flags out of range";
+        case SS_ERR_STRIDE: return "strides negative or rows overlap";
+        case SS_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case SS_ERR_DEVICE: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+int specsteer_version(void) { return 100; }
+
+}  // extern "C"

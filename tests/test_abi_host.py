@@ -1,0 +1,125 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+and rejects bad arguments on the host before anything is enqueued (no GPU work happens in
+any of these calls: argument errors return first, and batch == 0 is a no-op)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2603_16219_amd import binding
+
+    return binding.library()
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2603_16219_amd import binding
+
+    return binding
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "specsteer.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(specsteer_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(lib):
+    names = declared_symbols()
+    assert names == ["specsteer_status_string", "specsteer_verify_block", "specsteer_version",
+                     "specsteer_workspace_bytes"]
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_status_strings(B):
+    assert B.version() >= 100
+    seen = {B.status_string(i) for i in range(8)}
+    assert len(seen) == 8 and B.status_string(0) == "ok" and B.status_string(99) == "unknown status"
+
+
+def test_params_struct_matches_header_layout(B):
+    # int32 x4, int64 x2, float x3, uint32: 48 bytes, strides 8-byte aligned at offset 16
+    assert ctypes.sizeof(B.SSParams) == 48
+    assert B.SSParams.stride_b.offset == 16 and B.SSParams.lambda_.offset == 32 and B.SSParams.flags.offset == 44
+
+
+def test_workspace_bytes(B):
+    import torch
+
+    p = B.make_params(256, 16, 128256, torch.bfloat16, lam=0.5, beta=0.8, temperature=0.7)
+    n = B.workspace_bytes(p)
+    assert n % 256 == 0 and 0 < n < 64 << 20
+    assert B.workspace_bytes(B.make_params(0, 0, 1, torch.float32, lam=0.5, beta=1.0, temperature=1.0)) > 0
+    for bad in (dict(batch=-1), dict(k_max=-1), dict(vocab=0), dict(vocab=(1 << 20) + 1), dict(k_max=1025)):
+        kw = dict(batch=4, k_max=4, vocab=100)
+        kw.update(bad)
+        assert B.workspace_bytes(B.make_params(kw["batch"], kw["k_max"], kw["vocab"], torch.float32, lam=0.5,
+                                               beta=1.0, temperature=1.0)) == 0
+    p.dtype = 7
+    assert B.workspace_bytes(p) == 0
+    assert B.library().specsteer_workspace_bytes(None) == 0
+
+
+def call(B, params, *, null=None, ws=256, ws_bytes=1 << 30):
+    """Invoke the entry point with fake, never-dereferenced device addresses."""
+    fake = {k: 4096 * (i + 1) for i, k in enumerate(
+        ["G", "S_ctx", "S_noctx", "draft", "draft_len", "uniforms", "accepted_len", "next_token", "ntl", "rec",
+         "dlp"])}
+    if null:
+        fake[null] = 0
+    v = lambda k: ctypes.c_void_p(fake[k])
+    return B.library().specsteer_verify_block(
+        v("G"), v("S_ctx"), v("S_noctx"), v("draft"), v("draft_len"), v("uniforms"),
+        ctypes.byref(params) if params is not None else None, v("accepted_len"), v("next_token"), v("ntl"),
+        v("rec"), v("dlp"), ctypes.c_void_p(ws), ctypes.c_size_t(ws_bytes), None)
+
+
+def test_argument_errors_are_reported_on_the_host(B):
+    import torch
+
+    def P(**kw):
+        base = dict(batch=0, k_max=4, vocab=1000, lam=0.5, beta=1.0, temperature=1.0, stride_b=0, stride_t=0, flags=0)
+        base.update(kw)
+        return B.make_params(base["batch"], base["k_max"], base["vocab"], torch.bfloat16, lam=base["lam"],
+                             beta=base["beta"], temperature=base["temperature"], stride_b=base["stride_b"],
+                             stride_t=base["stride_t"], flags=base["flags"])
+
+    OK, NULL, SHAPE, DTYPE, PARAM, STRIDE, WS = 0, 1, 2, 3, 4, 5, 6
+    assert call(B, P()) == OK  # batch == 0: validated, nothing launched
+    assert call(B, None) == NULL
+    for k in ("G", "S_ctx", "S_noctx", "draft", "uniforms", "accepted_len", "next_token"):
+        assert call(B, P(), null=k) == NULL, k
+    for k in ("draft_len", "ntl", "rec", "dlp"):  # optional pointers
+        assert call(B, P(), null=k) == OK, k
+    assert call(B, P(k_max=0), null="draft") == OK
+    assert call(B, P(batch=-1)) == SHAPE
+    assert call(B, P(vocab=0)) == SHAPE
+    assert call(B, P(k_max=2000)) == SHAPE
+    p = P()
+    p.dtype = 2
+    assert call(B, p) == DTYPE
+    for kw in (dict(lam=0.0), dict(lam=-1.0), dict(lam=float("inf")), dict(lam=float("nan")),
+               dict(temperature=0.0), dict(temperature=float("nan")), dict(beta=float("inf")), dict(flags=1)):
+        assert call(B, P(**kw)) == PARAM, kw
+    assert call(B, P(stride_t=999)) == STRIDE       # rows would overlap
+    assert call(B, P(stride_t=1000, stride_b=4999)) == STRIDE
+    assert call(B, P(stride_t=-8)) == STRIDE
+    assert call(B, P(stride_t=1008, stride_b=5 * 1008)) == OK
+    assert call(B, P(), ws=0) == WS
+    assert call(B, P(), ws=128) == WS               # not 256-byte aligned
+    assert call(B, P(batch=4), ws_bytes=16) == WS   # too small; rejected before any launch
+
+
+def test_python_wrapper_refuses_cpu_tensors(B):
+    import torch
+
+    x = torch.zeros(1, 2, 8)
+    with pytest.raises(ValueError):
+        B.verify_block(x, x, x, torch.zeros(1, 1, dtype=torch.int32), torch.zeros(1, 2))

@@ -1,0 +1,227 @@
+"""GPU parity: the HIP path, called through the C ABI, against the float64 oracle on the
+same seeded inputs.  Needs a real MI355X (pytest -m gpu)."""
+import numpy as np
+import pytest
+import torch
+
+import parity
+from paper_2603_16219_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2603_16219_amd import binding as b
+
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    b.library()
+    return b
+
+
+def run_both(binding, oracle, w, inp, seqs=None, rec=True):
+    out = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"],
+                               lam=w.lam, beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"],
+                               want_recovery_logprobs=rec, want_draft_logprobs=True)
+    torch.cuda.synchronize()
+    ora = parity.oracle_run(oracle, inp, lam=w.lam, beta=w.beta, temperature=w.temperature, seqs=seqs,
+                            want_recovery_logprobs=rec, num_threads=16)
+    rep = parity.compare(out, ora, inp["uniforms"], inp["draft_len"], seqs=seqs)
+    print(f"\n[{w.name}] {rep}", flush=True)
+    return out, ora, rep
+
+
+# ------------------------------------------------------------------ the five configs
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c3"])
+def test_config_full_size(binding, oracle, name):
+    w = W.WORKLOADS[name]
+    inp = W.generate(w, "cuda")
+    out, ora, rep = run_both(binding, oracle, w, inp)
+    assert 0 < rep["mean_accepted_len"] <= w.k_max
+
+
+def test_config_c4_ragged_full_size(binding, oracle):
+    w = W.WORKLOADS["c4"]
+    inp = W.generate(w, "cuda")
+    out, ora, rep = run_both(binding, oracle, w, inp)
+    n = out["accepted_len"].cpu()
+    assert torch.all(n <= inp["draft_len"].cpu()) and torch.all(n >= 0)
+
+
+def test_config_c5_full_size_sampled_sequences(binding, oracle):
+    w = W.WORKLOADS["c5"]
+    inp = W.generate(w, "cuda")
+    seqs = torch.arange(5, w.batch, 8, device="cuda")  # 64 of the 512 sequences go through the oracle
+    out, ora, rep = run_both(binding, oracle, w, inp, seqs=seqs, rec=True)
+    # properties that hold for every sequence at any size
+    n = out["accepted_len"].cpu().numpy()
+    tok = out["next_token"].cpu().numpy()
+    assert np.all((n >= 0) & (n <= w.k_max)) and np.all((tok >= 0) & (tok < w.vocab))
+    lp = out["recovery_logprobs"]
+    assert torch.allclose(torch.exp(lp.double()).sum(-1), torch.ones(w.batch, dtype=torch.float64, device="cuda"),
+                          atol=1e-5)
+    assert torch.allclose(lp.cpu()[torch.arange(w.batch), torch.from_numpy(tok).long()],
+                          out["next_token_logprob"].cpu(), atol=1e-5)
+
+
+# ------------------------------------------------------------------ shapes that stress tiling
+
+@pytest.mark.parametrize("vocab,pad", [(20011, 0), (20011, 5), (20008, 0), (2048, 0), (2049, 7), (777, 0),
+                                       (8, 0), (5, 3), (1, 0), (1, 7), (65, 0), (512 * 4 * 3 + 8, 0)])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_ragged_tails_and_alignment(binding, oracle, vocab, pad, dtype):
+    """pad > 0 stores rows with a padded stride (aligned fast path with a partial last vector
+    when the stride is a multiple of 16 bytes); pad == 0 with an odd vocabulary makes rows
+    unaligned and takes the element-wise path."""
+    base = W.scaled(W.WORKLOADS["c4"], batch=7, vocab=vocab + pad, k_max=5, name=f"tail{vocab}+{pad}{dtype}")
+    import dataclasses
+    base = dataclasses.replace(base, dtype=dtype)
+    inp = W.generate(base, "cuda")
+    if pad:
+        for k in ("G", "S_ctx", "S_noctx"):
+            inp[k][..., vocab:] = float("nan")  # the padding must never be read
+            inp[k] = inp[k][..., :vocab]
+        inp["draft"] = inp["draft"].clamp(max=vocab - 1)
+    inp["draft_len"] = torch.tensor([0, 1, 5, 3, 5, 2, 4], dtype=torch.int32, device="cuda")
+    w = dataclasses.replace(base, vocab=vocab)
+    run_both(binding, oracle, w, inp)
+
+
+def test_unaligned_base_pointers(binding, oracle):
+    w = W.scaled(W.WORKLOADS["c2"], batch=3, vocab=4096, k_max=4, name="unaligned")
+    inp = W.generate(w, "cuda")
+    for k in ("G", "S_ctx", "S_noctx"):
+        flat = torch.empty(inp[k].numel() + 3, dtype=inp[k].dtype, device="cuda")
+        view = flat[3:].view_as(inp[k])  # 6 bytes off a 16-byte boundary
+        view.copy_(inp[k])
+        inp[k] = view
+        assert inp[k].data_ptr() % 16 != 0
+    run_both(binding, oracle, w, inp)
+
+
+def test_no_drafts_and_single_sequence(binding, oracle):
+    w = W.scaled(W.WORKLOADS["c1"], batch=1, vocab=32000, k_max=0, name="k0")
+    inp = W.generate(w, "cuda")
+    out, ora, _ = run_both(binding, oracle, w, inp)
+    assert out["accepted_len"].item() == 0
+    w = W.scaled(W.WORKLOADS["c4"], batch=5, vocab=3000, k_max=3, name="allzero")
+    inp = W.generate(w, "cuda")
+    inp["draft_len"] = torch.zeros(5, dtype=torch.int32, device="cuda")
+    run_both(binding, oracle, w, inp)
+
+
+def test_long_draft_blocks_use_more_than_one_ballot(binding, oracle):
+    w = W.scaled(W.WORKLOADS["c4"], batch=3, vocab=1024, k_max=150, name="k150")
+    inp = W.generate(w, "cuda")
+    inp["draft_len"] = torch.tensor([150, 70, 129], dtype=torch.int32, device="cuda")
+    inp["uniforms"][:, :150] *= 0.02  # long accepted prefixes so the first rejection falls in a late ballot
+    out, ora, rep = run_both(binding, oracle, w, inp)
+    assert rep["mean_accepted_len"] > 20
+
+
+def test_padding_rows_and_slots_are_never_read(binding, oracle):
+    w = W.scaled(W.WORKLOADS["c4"], batch=16, vocab=8192, k_max=8, name="poison")
+    inp = W.generate(w, "cuda")
+    ref = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], lam=w.lam,
+                               beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"],
+                               want_recovery_logprobs=True, want_draft_logprobs=True)
+    L = inp["draft_len"].cpu()
+    n = ref["accepted_len"].cpu()
+    for b in range(w.batch):
+        for k in ("G", "S_noctx"):
+            inp[k][b, L[b] + 1:] = float("nan")
+        inp["S_ctx"][b, : n[b]] = float("nan")  # only the recovery row of S_ctx is ever touched
+        inp["S_ctx"][b, n[b] + 1:] = float("nan")
+        inp["draft"][b, L[b]:] = -123456
+        inp["uniforms"][b, L[b]: w.k_max] = float("nan")
+    got = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], lam=w.lam,
+                               beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"],
+                               want_recovery_logprobs=True, want_draft_logprobs=True)
+    for k in ref:
+        assert torch.equal(ref[k], got[k]), k
+    run_both(binding, oracle, w, inp)
+
+
+def test_bad_sequences_are_flagged(binding, oracle):
+    w = W.scaled(W.WORKLOADS["c4"], batch=6, vocab=4000, k_max=4, name="bad")
+    inp = W.generate(w, "cuda")
+    inp["draft_len"] = torch.tensor([4, 5, -1, 2, 3, 0], dtype=torch.int32, device="cuda")
+    inp["draft"][3, 1] = 4000
+    inp["draft"][4, 0] = -1
+    inp["draft"][0, 3] = 3999
+    out, ora, _ = run_both(binding, oracle, w, inp)
+    assert out["accepted_len"].cpu().tolist()[1:5] == [-1, -1, -1, -1]
+    assert out["accepted_len"][0].item() >= 0 and out["accepted_len"][5].item() == 0
+
+
+def test_extreme_logits_and_peaked_rows(binding, oracle):
+    import dataclasses
+    w = dataclasses.replace(W.scaled(W.WORKLOADS["c5"], batch=6, vocab=30000, k_max=4, name="peaked"), beta=2.5)
+    inp = W.generate(w, "cuda")
+    inp["G"][0:2] += 80.0
+    inp["S_ctx"][2:4] -= 80.0
+    inp["S_noctx"][1:3] += 64.0
+    run_both(binding, oracle, w, inp)
+    w2 = dataclasses.replace(w, dtype="f32", temperature=0.3, name="peaked32")
+    run_both(binding, oracle, w2, W.generate(w2, "cuda"))
+
+
+def test_strided_batch_view(binding, oracle):
+    w = W.scaled(W.WORKLOADS["c2"], batch=6, vocab=4096, k_max=5, name="strided")
+    inp = W.generate(w, "cuda")
+    for k in ("G", "S_ctx", "S_noctx"):
+        inp[k] = inp[k][::2, :4]  # every other sequence, first 4 rows: stride_b and stride_t both non-dense
+    inp["draft"] = inp["draft"][::2, :3].contiguous()
+    inp["uniforms"] = inp["uniforms"][::2, :4].contiguous()
+    w = W.scaled(w, batch=3, k_max=3)
+    run_both(binding, oracle, w, inp)
+
+
+def test_run_twice_bit_identical(binding):
+    w = W.scaled(W.WORKLOADS["c4"], batch=32, vocab=50000, k_max=8, name="twice")
+    inp = W.generate(w, "cuda")
+    outs = []
+    for _ in range(2):
+        outs.append(binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"],
+                                         lam=w.lam, beta=w.beta, temperature=w.temperature,
+                                         draft_len=inp["draft_len"], want_recovery_logprobs=True,
+                                         want_draft_logprobs=True))
+    torch.cuda.synchronize()
+    for k in outs[0]:
+        assert torch.equal(outs[0][k], outs[1][k]), k
+
+
+def test_lambda_sweep_matches_oracle(binding, oracle):
+    """The threshold values of the paper's sensitivity study."""
+    import dataclasses
+    base = W.scaled(W.WORKLOADS["c4"], batch=24, vocab=16384, k_max=8, name="lam")
+    inp = W.generate(base, "cuda")
+    prev = None
+    for lam in (1.0, 0.5, 0.1, 0.01):
+        w = dataclasses.replace(base, lam=lam, name=f"lam{lam}")
+        out, ora, rep = run_both(binding, oracle, w, inp)
+        if prev is not None:
+            assert rep["mean_accepted_len"] >= prev  # a smaller threshold accepts more
+        prev = rep["mean_accepted_len"]
+
+
+def test_sampling_edges_on_gpu(binding, oracle):
+    """Uniforms placed just inside both ends of every CDF interval of a 6-token row."""
+    V = 6
+    G = torch.tensor([[[0.5, -1.0, 2.0, 0.0, 1.5, -0.5]]], dtype=torch.float32, device="cuda")
+    z = torch.zeros_like(G)
+    p = torch.softmax(G[0, 0].double(), -1).cpu().numpy()
+    cdf = np.cumsum(p)
+    us, want = [0.0], [0]
+    for j in range(V - 1):
+        us += [float(np.float32(cdf[j] - 3e-6)), float(np.float32(cdf[j] + 3e-6))]
+        want += [j, j + 1]
+    us.append(float(np.nextafter(np.float32(1), np.float32(0))))
+    want.append(V - 1)
+    B = len(us)
+    Gb = G.expand(B, 1, V).contiguous()
+    out = binding.verify_block(Gb, torch.zeros_like(Gb), torch.zeros_like(Gb),
+                               torch.zeros(B, 0, dtype=torch.int32, device="cuda"),
+                               torch.tensor(us, dtype=torch.float32, device="cuda").view(B, 1))
+    assert out["next_token"].cpu().tolist() == want
