@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the verify-and-recover block on one MI355X.
+
+One step = one call of specsteer_verify_block (row log-sum-exp pass, ratio test, first
+rejection, recovery distribution, sampling) over one batch of synthetic logits already
+resident in HBM.  Prints ONE JSON line: verified draft positions per second, the HBM
+roofline of the dominant kernel (row_lse) measured with HIP events on the launch stream,
+and the float64 oracle timed on the host cores as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def describe(w) -> str:
+    k = f"ragged K_b~U{{1..{w.k_max}}} k_max={w.k_max}" if w.ragged else f"K={w.k_max}"
+    return (f"{w.name}: B={w.batch} {k} V={w.vocab} {w.dtype} sigma={w.sigma} T={w.temperature} "
+            f"beta={w.beta} lambda={w.lam}")
+
+
+def read_traffic(workload: str):
+    """HBM bytes per row_lse launch from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"row_lse_{workload}_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    for line in open(path):
+        if line.startswith("hbm_bytes_per_launch_"):
+            k, v = line.split(":", 1)
+            vals[k.strip()] = float(v.split()[0])
+    if "hbm_bytes_per_launch_read" in vals:
+        return vals["hbm_bytes_per_launch_read"] + vals.get("hbm_bytes_per_launch_write", 0.0)
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c4", help="c1..c5 (c4 is the configuration the target is quoted on)")
+    ap.add_argument("--sets", type=int, default=2, help="rotating input sets")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--lam", type=float, default=None, help="override the verification threshold")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the block shards by sequence with no "
+              "communication; multi-GPU figures are not part of it). Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+
+    from paper_2603_16219_amd import binding, workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 3
+    binding.library()
+    dev = torch.device("cuda:0")
+    w = W.WORKLOADS[args.workload]
+    if args.lam is not None:
+        import dataclasses
+        w = dataclasses.replace(w, lam=args.lam)
+    esz = 2 if w.dtype == "bf16" else 4
+
+    sets = [W.generate(w, dev, seed_shift=i) for i in range(max(1, args.sets))]
+    B, kmax, V = w.batch, w.k_max, w.vocab
+    params = binding.make_params(B, kmax, V, W.torch_dtype(w.dtype), lam=w.lam, beta=w.beta,
+                                 temperature=w.temperature)
+    ws = torch.empty(max(256, binding.workspace_bytes(params)), dtype=torch.uint8, device=dev)
+    acc = torch.empty(B, dtype=torch.int32, device=dev)
+    tok = torch.empty(B, dtype=torch.int32, device=dev)
+    tlp = torch.empty(B, dtype=torch.float32, device=dev)
+
+    def step(i, timed=False):
+        s = sets[i % len(sets)]
+        return binding.verify_block_raw(s["G"], s["S_ctx"], s["S_noctx"], s["draft"], s["draft_len"], s["uniforms"],
+                                        params, acc, tok, tlp, None, None, ws, timed=timed)
+
+    positions = [int(s["draft_len"].sum().item()) if s["draft_len"] is not None else B * kmax for s in sets]
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    pos_total = sum(positions[i % len(sets)] for i in range(args.steps))
+    ms_per_step = elapsed / args.steps * 1e3
+
+    # per-kernel durations: HIP events recorded on the launch stream, inside the library
+    n_timed = min(args.steps, 20)
+    stage = {k: 0.0 for k in binding.STAGES}
+    lse_bytes = 0.0
+    step_bytes = 0.0
+    bonus_frac = 0.0
+    for i in range(n_timed):
+        ms = step(i, timed=True)
+        for k in stage:
+            stage[k] += ms[k] / n_timed
+        s = sets[i % len(sets)]
+        K = s["draft_len"] if s["draft_len"] is not None else torch.full((B,), kmax, dtype=torch.int32, device=dev)
+        n_bonus = int((acc == K).sum().item())
+        # row pass: two rows of V logits per verified position
+        lse_bytes += 2.0 * positions[i % len(sets)] * V * esz / n_timed
+        # whole step, unique bytes: the row pass, the S_ctx recovery row of every sequence, and the
+        # G / S_noctx bonus rows of fully accepted sequences (a rejected row was already read by the row pass)
+        step_bytes += (2.0 * positions[i % len(sets)] + B + 2.0 * n_bonus) * V * esz / n_timed
+        bonus_frac += n_bonus / B / n_timed
+    lse_gbs = lse_bytes / (stage["row_lse"] * 1e-3) / 1e9 if stage["row_lse"] > 0 else 0.0
+
+    out = {
+        "metric": "verified draft positions/sec",
+        "value": pos_total / elapsed,
+        "unit": "positions/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": describe(w), "logits_dtype": w.dtype, "input_sets": len(sets),
+                   "positions_per_step": positions[0], "bonus_fraction": round(bonus_frac, 4)},
+        "roofline": {
+            "bound": "hbm", "kernel": "row_lse_kernel", "achieved": lse_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": lse_gbs / HBM_PEAK_GBS, "traffic": read_traffic(w.name),
+            "algorithmic_bytes_per_launch": lse_bytes, "avg_launch_ms": stage["row_lse"],
+        },
+        "stages_ms": {k: round(v, 5) for k, v in stage.items()},
+        "whole_step": {"algorithmic_bytes": step_bytes, "GB/s": step_bytes / (ms_per_step * 1e-3) / 1e9,
+                       "frac_of_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        import parity
+
+        oracle.build()
+        s = sets[0]
+        # bounded sample: whole sequences, chosen so the oracle does roughly 10-30 s of CPU work
+        exps_per_seq = (2.0 * positions[0] / B + 1.5) * V
+        nseq = int(max(1, min(B, 6e8 // max(exps_per_seq, 1))))
+        threads = min(oracle.max_threads(), int(os.environ.get("OMP_NUM_THREADS", "16")), nseq)
+        seqs = torch.arange(nseq, device=dev)
+        host = {k: (None if v is None else v[:nseq].cpu()) for k, v in s.items()}
+        t1 = time.perf_counter()
+        ora = oracle.verify_block(host["G"], host["S_ctx"], host["S_noctx"], host["draft"], host["uniforms"],
+                                  lam=w.lam, beta=w.beta, temperature=w.temperature, draft_len=host["draft_len"],
+                                  want_recovery_logprobs=False, num_threads=threads)
+        cpu_s = time.perf_counter() - t1
+        cpu_pos = int(host["draft_len"].sum().item()) if host["draft_len"] is not None else nseq * kmax
+        out["cpu_baseline"] = {
+            "value": cpu_pos / cpu_s, "unit": "positions/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {nseq} of {B} sequences of {w.name} ({cpu_pos} positions), float64 oracle, "
+                      f"{threads} OpenMP threads over sequences, {cpu_s:.2f} s wall",
+        }
+        # parity of the same step against the oracle, reported beside the timing
+        dlp = torch.empty(B, kmax, 2, dtype=torch.float32, device=dev)
+        binding.verify_block_raw(s["G"], s["S_ctx"], s["S_noctx"], s["draft"], s["draft_len"], s["uniforms"], params,
+                                 acc, tok, tlp, None, dlp, ws)
+        torch.cuda.synchronize()
+        rep = parity.compare({"accepted_len": acc, "next_token": tok, "next_token_logprob": tlp,
+                              "draft_logprobs": dlp}, ora, s["uniforms"], s["draft_len"], seqs=seqs)
+        out["parity"] = rep
+
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -123,6 +123,28 @@ ss_status specsteer_verify_block(const void *G, const void *S_ctx, const void *S
                                  float *draft_logprobs, void *workspace, size_t workspace_bytes,
                                  void *stream);
 
+/*
+ * Benchmark variant of specsteer_verify_block (same operation: Algorithm 1 phases 2-3,
+ * Eq. 7, Eq. 8; same arguments, same outputs, same errors).  It brackets each kernel with
+ * HIP events recorded on `stream`, WAITS for the last one, and writes the elapsed
+ * milliseconds of each stage to the host array stage_ms[SS_NUM_STAGES]:
+ *   [SS_STAGE_PREP]    ragged row list (0 when draft_len is NULL),
+ *   [SS_STAGE_ROW_LSE] the log-sum-exp pass over every valid row of G and S_noctx,
+ *   [SS_STAGE_RECOVER] ratio test, first rejection, recovery distribution and sampling.
+ * Creates and destroys its events inside the call, so it is not for latency-critical use.
+ */
+#define SS_STAGE_PREP 0
+#define SS_STAGE_ROW_LSE 1
+#define SS_STAGE_RECOVER 2
+#define SS_NUM_STAGES 3
+ss_status specsteer_verify_block_timed(const void *G, const void *S_ctx, const void *S_noctx,
+                                       const int32_t *draft, const int32_t *draft_len,
+                                       const float *uniforms, const ss_params *params,
+                                       int32_t *accepted_len, int32_t *next_token,
+                                       float *next_token_logprob, float *recovery_logprobs,
+                                       float *draft_logprobs, void *workspace,
+                                       size_t workspace_bytes, void *stream, float *stage_ms);
+
 /* Static, human-readable name of an ss_status value. */
 const char *specsteer_status_string(int status);
 

@@ -56,6 +56,8 @@ def library() -> ctypes.CDLL:
         lib.specsteer_verify_block.argtypes = (
             [ctypes.c_void_p] * 6 + [ctypes.POINTER(SSParams)] + [ctypes.c_void_p] * 6
             + [ctypes.c_size_t, ctypes.c_void_p])
+        lib.specsteer_verify_block_timed.restype = ctypes.c_int
+        lib.specsteer_verify_block_timed.argtypes = lib.specsteer_verify_block.argtypes + [ctypes.c_void_p]
         lib.specsteer_status_string.restype = ctypes.c_char_p
         lib.specsteer_status_string.argtypes = [ctypes.c_int]
         lib.specsteer_version.restype = ctypes.c_int
@@ -87,20 +89,31 @@ def _ptr(t: Optional[torch.Tensor]):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
+STAGES = ("prep", "row_lse", "recover")
+
+
 def verify_block_raw(G, S_ctx, S_noctx, draft, draft_len, uniforms, params: SSParams, accepted_len,
                      next_token, next_token_logprob, recovery_logprobs, draft_logprobs, workspace,
-                     stream: Optional[int] = None) -> None:
-    """Thin call: every tensor is passed by its device pointer, nothing is checked or copied here."""
+                     stream: Optional[int] = None, timed: bool = False):
+    """Thin call: every tensor is passed by its device pointer, nothing is checked or copied here.
+    With ``timed`` it calls specsteer_verify_block_timed (which waits for the stream) and returns
+    the per-stage milliseconds as a dict."""
     if stream is None:
         stream = torch.cuda.current_stream(G.device).cuda_stream
-    rc = library().specsteer_verify_block(
+    args = [
         _ptr(G), _ptr(S_ctx), _ptr(S_noctx), _ptr(draft), _ptr(draft_len), _ptr(uniforms),
         ctypes.byref(params), _ptr(accepted_len), _ptr(next_token), _ptr(next_token_logprob),
         _ptr(recovery_logprobs), _ptr(draft_logprobs), _ptr(workspace),
         0 if workspace is None else workspace.numel() * workspace.element_size(),
-        ctypes.c_void_p(stream))
+        ctypes.c_void_p(stream)]
+    if timed:
+        ms = (ctypes.c_float * len(STAGES))()
+        rc = library().specsteer_verify_block_timed(*args, ctypes.cast(ms, ctypes.c_void_p))
+    else:
+        rc = library().specsteer_verify_block(*args)
     if rc != _STATUS_OK:
         raise SpecSteerError(rc, status_string(rc))
+    return dict(zip(STAGES, (float(x) for x in ms))) if timed else None
 
 
 def verify_block(G: torch.Tensor, S_ctx: torch.Tensor, S_noctx: torch.Tensor, draft: torch.Tensor,

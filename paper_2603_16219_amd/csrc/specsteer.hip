@@ -682,10 +682,12 @@ int device_cu_count() {
 
 template <int DT, int VEC, int VECFAST>
 hipError_t launch_all(const LseArgs& la, const RecArgs& ra, const int32_t* draft_len, int32_t* row_off,
-                      hipStream_t stream) {
+                      hipStream_t stream, hipEvent_t* ev) {
     const int B = ra.B, kmax = ra.kmax, V = ra.V;
+    if (ev) hipEventRecord(ev[0], stream);
     if (draft_len && kmax > 0)
         hipLaunchKernelGGL(prep_rows_kernel, dim3(1), dim3(1024), 0, stream, draft_len, B, kmax, row_off);
+    if (ev) hipEventRecord(ev[1], stream);
     const long items = (long)B * kmax * 2 * la.NS;
     if (items > 0) {
         const long per_wg = kLseThreads / kWave;
@@ -694,14 +696,22 @@ hipError_t launch_all(const LseArgs& la, const RecArgs& ra, const int32_t* draft
         if (wgs > cap) wgs = cap;
         hipLaunchKernelGGL((row_lse_kernel<DT, VEC, VECFAST>), dim3((unsigned)wgs), dim3(kLseThreads), 0, stream, la);
     }
+    if (ev) hipEventRecord(ev[2], stream);
     const long nvec = V / VEC;
     const long nch = (nvec + kWave * kChunkSteps - 1) / (kWave * kChunkSteps);
     const size_t smem = (size_t)(nch + 1) * 8;
     // a long row is worth a full 16-wave workgroup; many sequences fill the chip either way
     const int nt = 1024;
     hipLaunchKernelGGL((accept_recover_kernel<DT, VEC>), dim3((unsigned)B), dim3(nt), smem, stream, ra);
+    if (ev) hipEventRecord(ev[3], stream);
     return hipGetLastError();
 }
+
+ss_status verify_block_impl(const void* G, const void* S_ctx, const void* S_noctx, const int32_t* draft,
+                            const int32_t* draft_len, const float* uniforms, const ss_params* params,
+                            int32_t* accepted_len, int32_t* next_token, float* next_token_logprob,
+                            float* recovery_logprobs, float* draft_logprobs, void* workspace,
+                            size_t workspace_bytes, void* stream, hipEvent_t* ev);
 
 }  // namespace
 
@@ -717,6 +727,46 @@ ss_status specsteer_verify_block(const void* G, const void* S_ctx, const void* S
                                  int32_t* accepted_len, int32_t* next_token, float* next_token_logprob,
                                  float* recovery_logprobs, float* draft_logprobs, void* workspace,
                                  size_t workspace_bytes, void* stream) {
+    return verify_block_impl(G, S_ctx, S_noctx, draft, draft_len, uniforms, params, accepted_len, next_token,
+                             next_token_logprob, recovery_logprobs, draft_logprobs, workspace, workspace_bytes,
+                             stream, nullptr);
+}
+
+ss_status specsteer_verify_block_timed(const void* G, const void* S_ctx, const void* S_noctx, const int32_t* draft,
+                                       const int32_t* draft_len, const float* uniforms, const ss_params* params,
+                                       int32_t* accepted_len, int32_t* next_token, float* next_token_logprob,
+                                       float* recovery_logprobs, float* draft_logprobs, void* workspace,
+                                       size_t workspace_bytes, void* stream, float* stage_ms) {
+    if (!stage_ms) return SS_ERR_NULL;
+    for (int i = 0; i < SS_NUM_STAGES; ++i) stage_ms[i] = 0.f;
+    hipEvent_t ev[SS_NUM_STAGES + 1];
+    int made = 0;
+    for (; made <= SS_NUM_STAGES; ++made)
+        if (hipEventCreate(&ev[made]) != hipSuccess) break;
+    ss_status st = SS_ERR_DEVICE;
+    if (made == SS_NUM_STAGES + 1) {
+        st = verify_block_impl(G, S_ctx, S_noctx, draft, draft_len, uniforms, params, accepted_len, next_token,
+                               next_token_logprob, recovery_logprobs, draft_logprobs, workspace, workspace_bytes,
+                               stream, ev);
+        if (st == SS_OK && params->batch > 0) {
+            if (hipEventSynchronize(ev[SS_NUM_STAGES]) != hipSuccess) st = SS_ERR_DEVICE;
+            for (int i = 0; st == SS_OK && i < SS_NUM_STAGES; ++i)
+                if (hipEventElapsedTime(&stage_ms[i], ev[i], ev[i + 1]) != hipSuccess) st = SS_ERR_DEVICE;
+        }
+    }
+    for (int i = 0; i < made; ++i) hipEventDestroy(ev[i]);
+    return st;
+}
+
+}  // extern "C"
+
+namespace {
+
+ss_status verify_block_impl(const void* G, const void* S_ctx, const void* S_noctx, const int32_t* draft,
+                            const int32_t* draft_len, const float* uniforms, const ss_params* params,
+                            int32_t* accepted_len, int32_t* next_token, float* next_token_logprob,
+                            float* recovery_logprobs, float* draft_logprobs, void* workspace,
+                            size_t workspace_bytes, void* stream, hipEvent_t* ev) {
     if (!params) return SS_ERR_NULL;
     if (params->dtype != SS_F32 && params->dtype != SS_BF16) return SS_ERR_DTYPE;
     if (!shape_ok(params)) return SS_ERR_SHAPE;
@@ -768,14 +818,18 @@ ss_status specsteer_verify_block(const void* G, const void* S_ctx, const void* S
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t err;
     if (params->dtype == SS_BF16) {
-        err = fast ? launch_all<SS_BF16, 8, 8>(la, ra, draft_len, row_off, s)
-                   : launch_all<SS_BF16, 1, 8>(la, ra, draft_len, row_off, s);
+        err = fast ? launch_all<SS_BF16, 8, 8>(la, ra, draft_len, row_off, s, ev)
+                   : launch_all<SS_BF16, 1, 8>(la, ra, draft_len, row_off, s, ev);
     } else {
-        err = fast ? launch_all<SS_F32, 4, 4>(la, ra, draft_len, row_off, s)
-                   : launch_all<SS_F32, 1, 4>(la, ra, draft_len, row_off, s);
+        err = fast ? launch_all<SS_F32, 4, 4>(la, ra, draft_len, row_off, s, ev)
+                   : launch_all<SS_F32, 1, 4>(la, ra, draft_len, row_off, s, ev);
     }
     return err == hipSuccess ? SS_OK : SS_ERR_DEVICE;
 }
+
+}  // namespace
+
+extern "C" {
 
 const char* specsteer_status_string(int status) {
     switch (status) {

@@ -32,8 +32,8 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol(lib):
     names = declared_symbols()
-    assert names == ["specsteer_status_string", "specsteer_verify_block", "specsteer_version",
-                     "specsteer_workspace_bytes"]
+    assert names == ["specsteer_status_string", "specsteer_verify_block", "specsteer_verify_block_timed",
+                     "specsteer_version", "specsteer_workspace_bytes"]
     for n in names:
         assert getattr(lib, n) is not None
 
