@@ -52,6 +52,8 @@ def main() -> int:
     ap.add_argument("--sets", type=int, default=2, help="rotating input sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--lam", type=float, default=None, help="override the verification threshold")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 1 GiB device copies (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the block shards by sequence with no "
@@ -88,6 +90,15 @@ def main() -> int:
                                         params, acc, tok, tlp, None, None, ws, timed=timed)
 
     positions = [int(s["draft_len"].sum().item()) if s["draft_len"] is not None else B * kmax for s in sets]
+
+    if args.calibrate_copy:
+        # a plain elementwise copy of known size: reads 1 GiB, writes 1 GiB per launch
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     for i in range(args.warmup):
         step(i)

@@ -30,6 +30,7 @@
 
 #include <cmath>
 #include <cstdint>
+#include <cstdlib>
 
 #include "specsteer.h"
 
@@ -37,15 +38,31 @@ namespace {
 
 constexpr int kWave = 64;
 constexpr int kLseThreads = 256;            // 4 independent waves per workgroup
-constexpr int kLseUnroll = 4;               // 16-byte loads in flight per lane
-constexpr int kMinSliceVecs = kWave * kLseUnroll;  // smallest slice: one unrolled group
-constexpr int kMaxSliceVecs = 2048;         // 32 KiB of logits per slice
+constexpr int kLseUnrollMin = 4;            // 16-byte loads in flight per lane
+constexpr int kLseWgPerCu = 4;              // persistent workgroups per CU: 8 waves/CU read fastest
+constexpr int kMinSliceVecs = kWave * kLseUnrollMin;  // smallest slice: one unrolled group
+constexpr int kMaxSliceVecs = 4096;         // 64 KiB of logits per slice
 constexpr int kMaxSlices = 64;
+constexpr int kMaxLdsBatch = 8192;          // ragged batches up to this size keep their row list in LDS
 constexpr int kChunkSteps = 4;              // recovery chunk = 4 wave-steps (2048 bf16 logits)
 constexpr int kEInit = -(1 << 29);          // "no logit seen yet" exponent reference
 constexpr float kEClamp = 5.0e8f;           // keeps (int)ceil(h*c) inside int32 for any finite h
 constexpr double kLn2 = 0.693147180559945309417232121458;
 constexpr double kLog2e = 1.442695040888963407359924681002;
+
+constexpr int kRecThreads = 256;            // recovery pass: 4 independent waves per workgroup
+constexpr int kRecWgPerCu = 4;
+
+// TEMPORARY tuning knobs (environment), removed once the values are fixed.
+inline int env_int(const char* name, int dflt) {
+    const char* e = getenv(name);
+    const int v = e ? atoi(e) : dflt;
+    return v < 1 ? dflt : v;
+}
+inline int tune_wg_per_cu() { static int v = env_int("SS_TUNE_WG", kLseWgPerCu); return v; }
+inline int tune_unroll() { static int v = env_int("SS_TUNE_U", 4); return v; }
+inline int tune_slice_max() { static int v = env_int("SS_TUNE_SLICE", kMaxSliceVecs); return v < kMinSliceVecs ? kMinSliceVecs : v; }
+inline int tune_rec_wg_per_cu() { static int v = env_int("SS_TUNE_RWG", kRecWgPerCu); return v; }
 
 struct Partial {
     int E;    // integer exponent reference of this slice
@@ -74,6 +91,15 @@ __device__ __forceinline__ int wave_max_i32(int v) {
     const int a = __builtin_amdgcn_readlane(v, 0), b = __builtin_amdgcn_readlane(v, 16);
     const int c = __builtin_amdgcn_readlane(v, 32), d = __builtin_amdgcn_readlane(v, 48);
     return max(max(a, b), max(c, d));
+}
+
+__device__ __forceinline__ int wave_sum_i32(int v) {
+    v += dpp_mov<kDppXor1>(v);
+    v += dpp_mov<kDppXor2>(v);
+    v += dpp_mov<kDppHalfMirror>(v);
+    v += dpp_mov<kDppMirror>(v);
+    return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) +
+           __builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48);
 }
 
 __device__ __forceinline__ float wave_sum_f32(float x) {
@@ -109,10 +135,31 @@ template <> struct RawT<SS_F32, 4> { using type = float4; };
 template <> struct RawT<SS_BF16, 1> { using type = unsigned short; };
 template <> struct RawT<SS_F32, 1> { using type = float; };
 
+// Logit rows are streamed once and never reused by the same kernel: non-temporal loads keep
+// them from displacing each other in L2 / Infinity Cache and measure ~12 % faster than plain
+// loads on a pure read of this size.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
 template <int DT, int VEC>
-__device__ __forceinline__ typename RawT<DT, VEC>::type ld_raw(const void* row, long vec) {
-    using R = typename RawT<DT, VEC>::type;
-    return reinterpret_cast<const R*>(row)[vec];
+__device__ __forceinline__ typename RawT<DT, VEC>::type ld_raw(const void* row, long vec);
+template <>
+__device__ __forceinline__ uint4 ld_raw<SS_BF16, 8>(const void* row, long vec) {
+    const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row) + vec);
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
+template <>
+__device__ __forceinline__ float4 ld_raw<SS_F32, 4>(const void* row, long vec) {
+    const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(row) + vec);
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+template <>
+__device__ __forceinline__ unsigned short ld_raw<SS_BF16, 1>(const void* row, long vec) {
+    return __builtin_nontemporal_load(reinterpret_cast<const unsigned short*>(row) + vec);
+}
+template <>
+__device__ __forceinline__ float ld_raw<SS_F32, 1>(const void* row, long vec) {
+    return __builtin_nontemporal_load(reinterpret_cast<const float*>(row) + vec);
 }
 
 __device__ __forceinline__ float bf16_lo(unsigned w) { return __uint_as_float(w << 16); }
@@ -177,19 +224,36 @@ __device__ __forceinline__ double rec_y(float g, float sp, float sm, double c, d
     return fma((double)g, c, ((double)sp - (double)sm) * bc);
 }
 
-template <int N>
-__device__ __forceinline__ void acc_add_f64(Acc& a, const double (&y)[N]) {
-    double m = y[0];
+// Recovery pass accumulate.  The exponent reference is advanced from a cheap fp32 estimate of
+// this vector's maximum; the term exponents themselves are formed in double,
+//     z = g*c + (sp - sm)*beta*c - E   (two fused multiply-adds, E folded into the first),
+// so the only roundings are the final conversion of the small number z to fp32 and the
+// exponential.  sp - sm is taken in fp32: exact for bf16 inputs whose exponents differ by
+// less than 16 (otherwise the smaller one is below 2^-16 of the larger and the difference
+// rounds by at most 2^-25 of it); fp32 inputs widen first.
+template <int DT, int N>
+__device__ __forceinline__ void acc_add_rec(Acc& a, const float (&hg)[N], const float (&hp)[N], const float (&hm)[N],
+                                            double c, double bc, float cf, float bcf) {
+    float d[N];
+    float m = -3.0e38f;
 #pragma unroll
-    for (int i = 1; i < N; ++i) m = fmax(m, y[i]);
-    const int En = max(a.E, exp_ref((float)m));
+    for (int i = 0; i < N; ++i) {
+        d[i] = hp[i] - hm[i];
+        m = fmaxf(m, fmaf(hg[i], cf, d[i] * bcf));
+    }
+    // the estimate is within a few 1e-5 of the exact exponent: half a unit of slack keeps z <= ~0.5
+    const int En = max(a.E, exp_ref(m));
     a.s = ldexpf(a.s, a.E - En);
     a.E = En;
-    const double dE = (double)En;
-    float t = 0.f;
+    const double nE = -(double)En;
+    float t0 = 0.f, t1 = 0.f;
 #pragma unroll
-    for (int i = 0; i < N; ++i) t += __builtin_amdgcn_exp2f((float)(y[i] - dE));
-    a.s += t;
+    for (int i = 0; i < N; ++i) {
+        const double dd = (DT == SS_BF16) ? (double)d[i] : ((double)hp[i] - (double)hm[i]);
+        const float z = (float)fma((double)hg[i], c, fma(dd, bc, nE));
+        if (i & 1) t1 += __builtin_amdgcn_exp2f(z); else t0 += __builtin_amdgcn_exp2f(z);
+    }
+    a.s += t0 + t1;
 }
 
 __device__ __forceinline__ Partial wave_combine(Acc a) {
@@ -198,18 +262,18 @@ __device__ __forceinline__ Partial wave_combine(Acc a) {
     return Partial{Em, S};
 }
 
-// ------------------------------------------------------------------ kernel: ragged row list
+// ------------------------------------------------------------------ ragged row list
 
-// row_off[b] = number of valid (sequence, position) rows before sequence b; row_off[B] = total.
+// off[b] = number of valid (sequence, position) rows before sequence b; off[B] = total.
 // A length outside [0, k_max] contributes no rows (the sequence is flagged later).
-__global__ __launch_bounds__(1024) void prep_rows_kernel(const int32_t* __restrict__ draft_len, int B, int kmax,
-                                                         int32_t* __restrict__ row_off) {
+// Called by every thread of a workgroup of NT threads (NT a multiple of 64, at most 1024);
+// `off` may be LDS or global memory.  Ends with a barrier, so `off` is readable on return.
+__device__ __forceinline__ void block_scan_lengths(const int32_t* __restrict__ draft_len, int B, int kmax,
+                                                   int* off, int NT) {
     __shared__ int wave_tot[16];
-    __shared__ int carry;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid == 0) carry = 0;
-    __syncthreads();
-    for (int b0 = 0; b0 < B; b0 += 1024) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NW = NT >> 6;
+    int carry = 0;
+    for (int b0 = 0; b0 < B; b0 += NT) {
         const int b = b0 + tid;
         int k = 0;
         if (b < B) {
@@ -224,14 +288,24 @@ __global__ __launch_bounds__(1024) void prep_rows_kernel(const int32_t* __restri
         }
         if (lane == 63) wave_tot[wave] = incl;
         __syncthreads();
-        int before = carry;
-        for (int w = 0; w < wave; ++w) before += wave_tot[w];
-        if (b < B) row_off[b] = before + incl - k;
-        __syncthreads();
-        if (tid == 1023) carry = before + incl;
+        int before = carry, all = 0;
+        for (int w = 0; w < NW; ++w) {
+            const int wt = wave_tot[w];
+            if (w < wave) before += wt;
+            all += wt;
+        }
+        if (b < B) off[b] = before + incl - k;
+        carry += all;
         __syncthreads();
     }
-    if (tid == 0) row_off[B] = carry;
+    if (tid == 0) off[B] = carry;
+    __syncthreads();
+}
+
+// Only for batches too large for the in-kernel LDS row list.
+__global__ __launch_bounds__(1024) void prep_rows_kernel(const int32_t* __restrict__ draft_len, int B, int kmax,
+                                                         int32_t* __restrict__ row_off) {
+    block_scan_lengths(draft_len, B, kmax, row_off, 1024);
 }
 
 // ------------------------------------------------------------------ kernel: row log-sum-exp partials
@@ -239,25 +313,42 @@ __global__ __launch_bounds__(1024) void prep_rows_kernel(const int32_t* __restri
 struct LseArgs {
     const void* G;
     const void* Sm;
-    const int32_t* row_off;  // NULL => every sequence has k_max rows
-    Partial* partial;        // [rows][2][NS]
-    long sb, st;             // element strides
+    const int32_t* draft_len;  // NULL => every sequence has k_max rows
+    int32_t* row_off;          // ragged: global copy of the row list, [B+1]
+    Partial* partial;          // [rows][2][NS]
+    long sb, st;               // element strides
     int B, kmax, V, NS;
-    int slice_vecs;          // vectors (of the fast path's width) per slice
+    int slice_vecs;            // vectors (of the fast path's width) per slice
+    int list_in_lds;           // ragged: build the row list in LDS (else row_off was filled by prep_rows)
     float c_hi, c_lo;
 };
 
-template <int DT, int VEC, int VECFAST>
+// Work item = (row, tensor, slice), flattened so that consecutive items are consecutive slices
+// of one row.  One wave per item, no communication between waves; the grid is persistent and
+// strides over the item list.  Ragged batches build the row list in LDS at kernel start
+// (every workgroup repeats the same small scan), so no separate launch is needed.
+// Workgroup 0 also publishes the row list for the recovery pass.
+template <int DT, int VEC, int VECFAST, int kLseUnroll>
 __global__ __launch_bounds__(kLseThreads) void row_lse_kernel(const LseArgs a) {
+    extern __shared__ int lds_off[];
     const int lane = threadIdx.x & 63;
     const int wave_global = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (kLseThreads / kWave) + (threadIdx.x >> 6)));
     const int waves_total = gridDim.x * (kLseThreads / kWave);
-    const int R = a.row_off ? a.row_off[a.B] : a.B * a.kmax;
+    const bool ragged = a.draft_len != nullptr;
+    const int* off = a.row_off;
+    if (ragged && a.list_in_lds) {
+        block_scan_lengths(a.draft_len, a.B, a.kmax, lds_off, kLseThreads);
+        off = lds_off;
+    }
+    if (blockIdx.x == 0 && ragged && a.list_in_lds)
+        for (int i = threadIdx.x; i <= a.B; i += kLseThreads) a.row_off[i] = lds_off[i];
+    const int R = ragged ? off[a.B] : a.B * a.kmax;
     const long items = (long)R * 2 * a.NS;
     // a slice is slice_vecs vectors of the fast width; the element-wise path covers the same logits
     const long slice_units = (long)a.slice_vecs * (VECFAST / VEC);
     const long nvec = a.V / VEC;
     const int tailc = a.V - (int)(nvec * VEC);
+    constexpr long kGroup = (long)kWave * kLseUnroll;
 
     for (long item = wave_global; item < items; item += waves_total) {
         const int k = (int)(item % a.NS);
@@ -265,14 +356,14 @@ __global__ __launch_bounds__(kLseThreads) void row_lse_kernel(const LseArgs a) {
         const int x = (int)(rx & 1);
         const int r = (int)(rx >> 1);
         int b, t;
-        if (a.row_off) {
-            int lo = 0, hi = a.B;  // largest b with row_off[b] <= r; row_off[B] = R > r
+        if (ragged) {
+            int lo = 0, hi = a.B;  // largest b with off[b] <= r; off[B] = R > r
             while (hi - lo > 1) {
                 const int mid = (lo + hi) >> 1;
-                if (a.row_off[mid] <= r) lo = mid; else hi = mid;
+                if (off[mid] <= r) lo = mid; else hi = mid;
             }
             b = lo;
-            t = r - a.row_off[b];
+            t = r - off[b];
         } else {
             b = r / a.kmax;
             t = r - b * a.kmax;
@@ -280,10 +371,11 @@ __global__ __launch_bounds__(kLseThreads) void row_lse_kernel(const LseArgs a) {
         const void* row = row_ptr<DT>(x ? a.Sm : a.G, (long)b * a.sb + (long)t * a.st);
         const long v0 = (long)k * slice_units;
         const long v1 = min(nvec, v0 + slice_units);
+        const long nfull = v1 > v0 ? (v1 - v0) / kGroup : 0;  // wave-uniform trip count
 
         Acc acc{kEInit, 0.f};
         long v = v0 + lane;
-        for (; v + (long)kWave * (kLseUnroll - 1) < v1; v += (long)kWave * kLseUnroll) {
+        for (long g = 0; g < nfull; ++g, v += kGroup) {
             typename RawT<DT, VEC>::type raw[kLseUnroll];
 #pragma unroll
             for (int j = 0; j < kLseUnroll; ++j) raw[j] = ld_raw<DT, VEC>(row, v + (long)kWave * j);
@@ -320,8 +412,11 @@ struct RecArgs {
     const int32_t* draft;
     const int32_t* draft_len;
     const float* uniforms;
-    const int32_t* row_off;
-    const Partial* partial;
+    const int32_t* row_off;  // ragged: [B+1] row list written by the row pass
+    const Partial* partial;  // [rows][2][NS] from the row pass
+    Partial* mass;           // [B][NC] one (E, s) per recovery chunk
+    double* log2Z;           // [B] log2 of the recovery normaliser (for the log-prob sweep)
+    int32_t* rec_row;        // [B] recovery row n_b, or -1 for a flagged sequence
     int32_t* accepted_len;
     int32_t* next_token;
     float* next_token_logprob;
@@ -329,18 +424,94 @@ struct RecArgs {
     float* draft_logprobs;
     long sb, st;
     int B, kmax, V, NS;
+    int NC;          // chunks per row (full chunks + one pseudo-chunk for the logits past the last vector)
+    int NG, CG;      // chunk groups per row, chunks per group
     double c;        // log2(e) / T
     double bc;       // beta * log2(e) / T
     double ln_lambda;
 };
 
-// log2 of sum_v 2^(h_v * c) for one row, from its slice partials.
+// log2 of sum_v 2^(h_v * c) for one row, from its slice partials.  Partials are fetched eight
+// at a time (one memory round trip per batch) and merged online in double.
 __device__ __forceinline__ double combine_partials(const Partial* p, int NS) {
-    int Em = p[0].E;
-    for (int k = 1; k < NS; ++k) Em = max(Em, p[k].E);
+    int Em = kEInit;
     double S = 0.0;
-    for (int k = 0; k < NS; ++k) S += ldexp((double)p[k].s, p[k].E - Em);
+    for (int k0 = 0; k0 < NS; k0 += 8) {
+        Partial q[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            q[j] = Partial{kEInit, 0.f};
+            if (k0 + j < NS) q[j] = p[k0 + j];
+        }
+        int Eb = q[0].E;
+#pragma unroll
+        for (int j = 1; j < 8; ++j) Eb = max(Eb, q[j].E);
+        if (Eb > Em) {
+            S = ldexp(S, Em - Eb);
+            Em = Eb;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) S += ldexp((double)q[j].s, q[j].E - Em);
+    }
     return (double)Em + log2(S);
+}
+
+// Phase 2 for one sequence, by one wave (lane = drafted position, 64 at a time): the ratio test
+// of Eq. 7 at every position and the first rejection by ballot.  Wave-uniform results.
+// With `publish` the wave also writes this sequence's draft log-probs.
+template <int DT>
+__device__ __forceinline__ void ratio_test_wave(const RecArgs& a, int b, int lane, bool publish, int& n, bool& bad) {
+    const int kmax = a.kmax, V = a.V;
+    // everything whose address does not depend on other loads is requested first, so the whole
+    // test costs two memory round trips: (length, row offset, draft ids, uniforms), then
+    // (slice partials, draft-token logits)
+    int y_first = -1;
+    float u_first = 0.f;
+    if (lane < kmax) {
+        y_first = a.draft[(long)b * kmax + lane];
+        u_first = a.uniforms[(long)b * (kmax + 1) + lane];
+    }
+    const int K = a.draft_len ? a.draft_len[b] : kmax;
+    const bool bad_len = (K < 0 || K > kmax);
+    int first_rej = bad_len ? 0 : K;
+    bool any_bad = bad_len;
+    const long r0 = (a.draft_len && kmax > 0) ? (long)a.row_off[b] : (long)b * kmax;
+    for (int t0 = 0; !bad_len && t0 < K; t0 += kWave) {
+        const int t = t0 + lane;
+        bool rej = false, oob = false;
+        if (t < K) {
+            const int y = t0 == 0 ? y_first : a.draft[(long)b * kmax + t];
+            const float u = t0 == 0 ? u_first : a.uniforms[(long)b * (kmax + 1) + t];
+            if (y < 0 || y >= V) {
+                oob = true;
+            } else {
+                const Partial* p = a.partial + (r0 + t) * 2 * a.NS;
+                const double LG = combine_partials(p, a.NS);
+                const double LS = combine_partials(p + a.NS, a.NS);
+                const long off = (long)b * a.sb + (long)t * a.st;
+                const double hG = (double)ld_elem<DT>(row_ptr<DT>(a.G, off), y);
+                const double hS = (double)ld_elem<DT>(row_ptr<DT>(a.Sm, off), y);
+                const double lpG = kLn2 * (hG * a.c - LG);  // log P_LLM(y_t)
+                const double lpS = kLn2 * (hS * a.c - LS);  // log P_SLM^-(y_t)
+                const double alpha = fmin(1.0, exp(lpG - lpS - a.ln_lambda));  // Eq. 7
+                rej = !((double)u <= alpha);
+                if (publish && a.draft_logprobs) {
+                    a.draft_logprobs[((long)b * kmax + t) * 2 + 0] = (float)lpG;
+                    a.draft_logprobs[((long)b * kmax + t) * 2 + 1] = (float)lpS;
+                }
+            }
+        }
+        any_bad = any_bad || (__ballot(oob) != 0ull);
+        const unsigned long long rmask = __ballot(rej);
+        if (rmask && first_rej == K) first_rej = t0 + first_lane(rmask);
+    }
+    n = first_rej;
+    bad = any_bad;
+    if (publish && a.draft_logprobs) {  // padded slots read 0, a flagged sequence reads NaN throughout
+        const int from = bad ? 0 : K;
+        const float fill = bad ? __int_as_float(0x7FC00000) : 0.f;
+        for (int i = from * 2 + lane; i < kmax * 2; i += kWave) a.draft_logprobs[(long)b * kmax * 2 + i] = fill;
+    }
 }
 
 // The logits one lane owns in step j of chunk c, as recovery exponents y.  Regular chunks hold
@@ -369,256 +540,297 @@ __device__ __forceinline__ int chunk_lane_y(const void* g, const void* sp, const
     return 1;
 }
 
+// (E, s) mass of recovery chunk c, by one wave: sum over the chunk of 2^(y - E).
 template <int DT, int VEC>
-__global__ __launch_bounds__(1024) void accept_recover_kernel(const RecArgs a) {
-    extern __shared__ int smem[];
-    __shared__ int sh_n, sh_bad;
-    __shared__ double sh_log2Z;
-
-    const int b = blockIdx.x;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int NT = blockDim.x, NW = NT >> 6;
-    const int kmax = a.kmax, V = a.V;
-
-    const int K = a.draft_len ? a.draft_len[b] : kmax;
-    const bool bad_len = (K < 0 || K > kmax);
-
-    // ---- phase 2: ratio test on every drafted position, first rejection by wave ballot
-    if (wave == 0) {
-        int first_rej = bad_len ? 0 : K;
-        bool any_bad = bad_len;
-        const long r0 = a.row_off ? a.row_off[b] : (long)b * kmax;
-        for (int t0 = 0; !bad_len && t0 < K; t0 += kWave) {
-            const int t = t0 + lane;
-            bool rej = false, oob = false;
-            if (t < K) {
-                const int y = a.draft[(long)b * kmax + t];
-                if (y < 0 || y >= V) {
-                    oob = true;
-                } else {
-                    const Partial* p = a.partial + (r0 + t) * 2 * a.NS;
-                    const double LG = combine_partials(p, a.NS);
-                    const double LS = combine_partials(p + a.NS, a.NS);
-                    const long off = (long)b * a.sb + (long)t * a.st;
-                    const double hG = (double)ld_elem<DT>(row_ptr<DT>(a.G, off), y);
-                    const double hS = (double)ld_elem<DT>(row_ptr<DT>(a.Sm, off), y);
-                    const double lpG = kLn2 * (hG * a.c - LG);  // log P_LLM(y_t)
-                    const double lpS = kLn2 * (hS * a.c - LS);  // log P_SLM^-(y_t)
-                    const double alpha = fmin(1.0, exp(lpG - lpS - a.ln_lambda));  // Eq. 7
-                    rej = !((double)a.uniforms[(long)b * (kmax + 1) + t] <= alpha);
-                    if (a.draft_logprobs) {
-                        a.draft_logprobs[((long)b * kmax + t) * 2 + 0] = (float)lpG;
-                        a.draft_logprobs[((long)b * kmax + t) * 2 + 1] = (float)lpS;
-                    }
-                }
-            }
-            any_bad = any_bad || (__ballot(oob) != 0ull);
-            const unsigned long long rmask = __ballot(rej);
-            if (rmask && first_rej == K) first_rej = t0 + first_lane(rmask);
-        }
-        if (lane == 0) {
-            sh_n = first_rej;
-            sh_bad = any_bad ? 1 : 0;
-        }
-    }
-    __syncthreads();
-    const int n = sh_n;
-    const bool bad = sh_bad != 0;
-
-    if (a.draft_logprobs) {  // padded slots read 0, a flagged sequence reads NaN throughout
-        const int from = bad ? 0 : K;
-        const float fill = bad ? __int_as_float(0x7FC00000) : 0.f;
-        for (int i = from * 2 + tid; i < kmax * 2; i += NT) a.draft_logprobs[(long)b * kmax * 2 + i] = fill;
-    }
-    if (bad) {
-        if (tid == 0) {
-            a.accepted_len[b] = -1;
-            a.next_token[b] = -1;
-            if (a.next_token_logprob) a.next_token_logprob[b] = __int_as_float(0x7FC00000);
-        }
-        return;
-    }
-
-    // ---- phase 3: one sweep over the three rows at position n, one (E, s) mass per chunk
-    const long off = (long)b * a.sb + (long)n * a.st;
-    const void* g = row_ptr<DT>(a.G, off);
-    const void* sp = row_ptr<DT>(a.Sp, off);
-    const void* sm = row_ptr<DT>(a.Sm, off);
-    const long nvec = V / VEC;
-    const int tailc = V - (int)(nvec * VEC);
-    const long nch = (nvec + kWave * kChunkSteps - 1) / (kWave * kChunkSteps);
-    const int NC = (int)nch + (tailc ? 1 : 0);
-    int* chE = smem;
-    float* chS = reinterpret_cast<float*>(smem + NC);
-
-    for (long c = wave; c < NC; c += NW) {
-        Acc acc{kEInit, 0.f};
-        if (c < nch) {
-            const long vbase = c * (long)(kWave * kChunkSteps) + lane;
-            typename RawT<DT, VEC>::type rg[kChunkSteps], rp[kChunkSteps], rm[kChunkSteps];
+__device__ __forceinline__ Partial chunk_mass(const void* g, const void* sp, const void* sm, long nvec, int tailc,
+                                              long nch, long c, int lane, double cc, double bc) {
+    const float cf = (float)cc, bcf = (float)bc;
+    Acc acc{kEInit, 0.f};
+    if (c < nch) {
+        const long vbase = c * (long)(kWave * kChunkSteps) + lane;
+        typename RawT<DT, VEC>::type rg[kChunkSteps], rp[kChunkSteps], rm[kChunkSteps];
 #pragma unroll
-            for (int j = 0; j < kChunkSteps; ++j) {
-                const long v = vbase + (long)j * kWave;
-                if (v < nvec) {
-                    rg[j] = ld_raw<DT, VEC>(g, v);
-                    rp[j] = ld_raw<DT, VEC>(sp, v);
-                    rm[j] = ld_raw<DT, VEC>(sm, v);
-                }
+        for (int j = 0; j < kChunkSteps; ++j) {
+            const long v = vbase + (long)j * kWave;
+            if (v < nvec) {
+                rg[j] = ld_raw<DT, VEC>(g, v);
+                rp[j] = ld_raw<DT, VEC>(sp, v);
+                rm[j] = ld_raw<DT, VEC>(sm, v);
             }
+        }
 #pragma unroll
-            for (int j = 0; j < kChunkSteps; ++j) {
-                const long v = vbase + (long)j * kWave;
-                if (v < nvec) {
-                    float hg[VEC], hp[VEC], hm[VEC];
-                    unpack(rg[j], hg);
-                    unpack(rp[j], hp);
-                    unpack(rm[j], hm);
-                    double y[VEC];
-#pragma unroll
-                    for (int i = 0; i < VEC; ++i) y[i] = rec_y(hg[i], hp[i], hm[i], a.c, a.bc);
-                    acc_add_f64<VEC>(acc, y);
-                }
+        for (int j = 0; j < kChunkSteps; ++j) {
+            const long v = vbase + (long)j * kWave;
+            if (v < nvec) {
+                float hg[VEC], hp[VEC], hm[VEC];
+                unpack(rg[j], hg);
+                unpack(rp[j], hp);
+                unpack(rm[j], hm);
+                acc_add_rec<DT, VEC>(acc, hg, hp, hm, cc, bc, cf, bcf);
             }
-        } else if (lane < tailc) {
-            const long e = nvec * VEC + lane;
-            double y[1] = {rec_y(ld_elem<DT>(g, e), ld_elem<DT>(sp, e), ld_elem<DT>(sm, e), a.c, a.bc)};
-            acc_add_f64<1>(acc, y);
         }
-        const Partial p = wave_combine(acc);
-        if (lane == 0) {
-            chE[c] = p.E;
-            chS[c] = p.s;
-        }
+    } else if (lane < tailc) {
+        const long e = nvec * VEC + lane;
+        const float hg[1] = {ld_elem<DT>(g, e)}, hp[1] = {ld_elem<DT>(sp, e)}, hm[1] = {ld_elem<DT>(sm, e)};
+        acc_add_rec<DT, 1>(acc, hg, hp, hm, cc, bc, cf, bcf);
     }
-    __syncthreads();
+    return wave_combine(acc);
+}
 
-    // ---- locate u*Z among the chunk masses (double), then walk that one chunk again
-    if (wave == 0) {
-        int Em = kEInit;
-        for (int c = lane; c < NC; c += kWave) Em = max(Em, chE[c]);
-        const int Estar = wave_max_i32(Em);
-        const int per = (NC + kWave - 1) / kWave;
-        const int lo = min(lane * per, NC), hi = min(lo + per, NC);
-        double lsum = 0.0;
-        for (int c = lo; c < hi; ++c) lsum += ldexp((double)chS[c], chE[c] - Estar);
-        const double incl = wave_incl_scan_f64(lsum, lane);
-        const double total = __shfl(incl, 63, kWave);
-        double excl = __shfl_up(incl, 1, kWave);
-        if (lane == 0) excl = 0.0;
-        const double us = (double)a.uniforms[(long)b * (kmax + 1) + kmax];
-        const double target = us * total;
+// Inverse-CDF draw for one sequence by one wave, once every chunk mass of its recovery row is
+// known: a double-precision scan over the chunk masses finds the chunk holding u*Z, and only
+// that chunk is read again to pick the token.
+template <int DT, int VEC>
+__device__ __forceinline__ void sample_wave(const RecArgs& a, int b, int n, int lane, const void* g, const void* sp,
+                                            const void* sm, long nvec, int tailc, long nch) {
+    const int NC = a.NC;
+    const Partial* tab = a.mass + (long)b * NC;
+    const double us = (double)a.uniforms[(long)b * (a.kmax + 1) + a.kmax];  // issued with the first table loads
+    // Each lane owns a contiguous run of `per` chunks.  Up to kTabRegs per lane (any realistic
+    // vocabulary) they are fetched into registers in one round trip; longer runs re-read memory.
+    constexpr int kTabRegs = 4;
+    const int per = (NC + kWave - 1) / kWave;
+    const int lo = min(lane * per, NC), hi = min(lo + per, NC);
+    const bool cached = per <= kTabRegs;
+    Partial t[kTabRegs];
+#pragma unroll
+    for (int i = 0; i < kTabRegs; ++i) {
+        t[i] = Partial{kEInit, 0.f};
+        if (cached && lo + i < hi) t[i] = tab[lo + i];
+    }
+    int Em = kEInit;
+    if (cached) {
+#pragma unroll
+        for (int i = 0; i < kTabRegs; ++i) Em = max(Em, t[i].E);
+    } else {
+        for (int c = lo; c < hi; ++c) Em = max(Em, tab[c].E);
+    }
+    const int Estar = wave_max_i32(Em);
+    double lsum = 0.0;
+    if (cached) {
+#pragma unroll
+        for (int i = 0; i < kTabRegs; ++i) lsum += ldexp((double)t[i].s, t[i].E - Estar);
+    } else {
+        for (int c = lo; c < hi; ++c) lsum += ldexp((double)tab[c].s, tab[c].E - Estar);
+    }
+    const double incl = wave_incl_scan_f64(lsum, lane);
+    const double total = __shfl(incl, 63, kWave);
+    double excl = __shfl_up(incl, 1, kWave);
+    if (lane == 0) excl = 0.0;
+    const double target = us * total;
 
-        int cfound = -1, clast = -1;
-        double cbase = 0.0, cum = excl;
-        for (int c = lo; c < hi; ++c) {
-            const double m = ldexp((double)chS[c], chE[c] - Estar);
-            if (m > 0.0) clast = c;
-            const double cum2 = cum + m;
-            if (cfound < 0 && cum2 > target) {
-                cfound = c;
-                cbase = cum;
+    int cfound = -1, clast = -1;
+    double cbase = 0.0, cum = excl;
+    auto visit = [&](int c, const Partial& q) {
+        const double m = ldexp((double)q.s, q.E - Estar);
+        if (m > 0.0) clast = c;
+        const double cum2 = cum + m;
+        if (cfound < 0 && cum2 > target) {
+            cfound = c;
+            cbase = cum;
+        }
+        cum = cum2;
+    };
+    if (cached) {
+#pragma unroll
+        for (int i = 0; i < kTabRegs; ++i)
+            if (lo + i < hi) visit(lo + i, t[i]);
+    } else {
+        for (int c = lo; c < hi; ++c) visit(c, tab[c]);
+    }
+    const unsigned long long fmask = __ballot(cfound >= 0);
+    int cstar;
+    double base;
+    bool take_last = false;  // the uniform is not below the total mass (u >= 1 or not a number)
+    if (fmask) {
+        const int L = first_lane(fmask);
+        cstar = __shfl(cfound, L, kWave);
+        base = __shfl(cbase, L, kWave);
+    } else {
+        cstar = max(wave_max_i32(clast), 0);
+        base = 0.0;
+        take_last = true;
+    }
+
+    const double dE = (double)Estar;
+    const int nsteps = (cstar < nch) ? kChunkSteps : 1;
+    // fetch the whole chunk first (one round trip), then walk it step by step
+    double yy[kChunkSteps][VEC];
+    long firsts[kChunkSteps];
+    int cnts[kChunkSteps];
+#pragma unroll
+    for (int j = 0; j < kChunkSteps; ++j) {
+        cnts[j] = 0;
+        firsts[j] = 0;
+        if (j < nsteps)
+            cnts[j] = chunk_lane_y<DT, VEC>(g, sp, sm, nvec, tailc, nch, cstar, j, lane, a.c, a.bc, yy[j], firsts[j]);
+    }
+    double run = base;
+    long tok = -1, lastpos = -1;
+    double ytok = 0.0, ylast = 0.0;
+#pragma unroll
+    for (int j = 0; j < kChunkSteps; ++j) {
+        if (j >= nsteps || tok >= 0) continue;
+        const int cnt = cnts[j];
+        const long first = firsts[j];
+        double p[VEC];
+        double ls = 0.0;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            p[i] = (i < cnt) ? (double)__builtin_amdgcn_exp2f((float)(yy[j][i] - dE)) : 0.0;
+            ls += p[i];
+            if (i < cnt && p[i] > 0.0) {
+                lastpos = first + i;
+                ylast = yy[j][i];
             }
-            cum = cum2;
         }
-        const unsigned long long fmask = __ballot(cfound >= 0);
-        int cstar;
-        double base;
-        bool take_last = false;  // the uniform is not below the total mass (u >= 1 or not a number)
-        if (fmask) {
-            const int L = first_lane(fmask);
-            cstar = __shfl(cfound, L, kWave);
-            base = __shfl(cbase, L, kWave);
-        } else {
-            cstar = max(wave_max_i32(clast), 0);
-            base = 0.0;
-            take_last = true;
-        }
-
-        const double dE = (double)Estar;
-        const int nsteps = (cstar < nch) ? kChunkSteps : 1;
-        double run = base;
-        long tok = -1, lastpos = -1;
-        double ytok = 0.0, ylast = 0.0;
-        for (int j = 0; j < nsteps && tok < 0; ++j) {
-            double y[VEC];
-            long first;
-            const int cnt = chunk_lane_y<DT, VEC>(g, sp, sm, nvec, tailc, nch, cstar, j, lane, a.c, a.bc, y, first);
-            double p[VEC];
-            double ls = 0.0;
+        const double inc = wave_incl_scan_f64(ls, lane);
+        double before = __shfl_up(inc, 1, kWave);
+        if (lane == 0) before = 0.0;
+        before += run;
+        long mytok = -1;
+        double myy = 0.0, cw = before;
+        if (!take_last) {
 #pragma unroll
             for (int i = 0; i < VEC; ++i) {
-                p[i] = (i < cnt) ? (double)__builtin_amdgcn_exp2f((float)(y[i] - dE)) : 0.0;
-                ls += p[i];
-                if (i < cnt && p[i] > 0.0) {
-                    lastpos = first + i;
-                    ylast = y[i];
+                cw += p[i];
+                if (mytok < 0 && i < cnt && cw > target) {
+                    mytok = first + i;
+                    myy = yy[j][i];
                 }
             }
-            const double inc = wave_incl_scan_f64(ls, lane);
-            double before = __shfl_up(inc, 1, kWave);
-            if (lane == 0) before = 0.0;
-            before += run;
-            long mytok = -1;
-            double myy = 0.0, cw = before;
-            if (!take_last) {
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) {
-                    cw += p[i];
-                    if (mytok < 0 && i < cnt && cw > target) {
-                        mytok = first + i;
-                        myy = y[i];
-                    }
-                }
-            }
-            const unsigned long long hmask = __ballot(mytok >= 0);
-            if (hmask) {
-                const int L = first_lane(hmask);
-                tok = __shfl(mytok, L, kWave);
-                ytok = __shfl(myy, L, kWave);
-            }
-            run += __shfl(inc, 63, kWave);
         }
-        if (tok < 0) {
-            // rounding between the chunk table and the re-read (or take_last): the last logit of
-            // the chunk that still carries probability
-            long best = lastpos;
-#pragma unroll
-            for (int d = 1; d < kWave; d <<= 1) best = max(best, __shfl_xor(best, d, kWave));
-            const unsigned long long omask = __ballot(lastpos == best && best >= 0);
-            if (omask) {
-                tok = best;
-                ytok = __shfl(ylast, first_lane(omask), kWave);
-            } else {  // unreachable for finite logits; keep the index valid
-                tok = min((long)cstar * (kWave * kChunkSteps * VEC), (long)V - 1);
-                ytok = dE;
-            }
+        const unsigned long long hmask = __ballot(mytok >= 0);
+        if (hmask) {
+            const int L = first_lane(hmask);
+            tok = __shfl(mytok, L, kWave);
+            ytok = __shfl(myy, L, kWave);
         }
-        const double log2Z = dE + log2(total);
-        if (lane == 0) {
-            sh_log2Z = log2Z;
-            a.accepted_len[b] = n;
-            a.next_token[b] = (int32_t)tok;
-            if (a.next_token_logprob) a.next_token_logprob[b] = (float)(kLn2 * (ytok - log2Z));
+        run += __shfl(inc, 63, kWave);
+    }
+    if (tok < 0) {
+        // rounding between the chunk table and the re-read (or take_last): the last logit of
+        // the chunk that still carries probability
+        long best = lastpos;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) best = max(best, __shfl_xor(best, d, kWave));
+        const unsigned long long omask = __ballot(lastpos == best && best >= 0);
+        if (omask) {
+            tok = best;
+            ytok = __shfl(ylast, first_lane(omask), kWave);
+        } else {  // unreachable for finite logits; keep the index valid
+            tok = min((long)cstar * (kWave * kChunkSteps * VEC), (long)a.V - 1);
+            ytok = dE;
         }
     }
+    const double log2Z = dE + log2(total);
+    if (lane == 0) {
+        a.log2Z[b] = log2Z;
+        a.accepted_len[b] = n;
+        a.next_token[b] = (int32_t)tok;
+        if (a.next_token_logprob) a.next_token_logprob[b] = (float)(kLn2 * (ytok - log2Z));
+    }
+}
 
-    // ---- optional: the whole log Softmax(h_rec / T) row
-    if (a.recovery_logprobs) {
-        __syncthreads();
-        const double log2Z = sh_log2Z;
-        float* out = a.recovery_logprobs + (long)b * V;
-        for (long v = tid; v < nvec; v += NT) {
-            float hg[VEC], hp[VEC], hm[VEC];
-            unpack(ld_raw<DT, VEC>(g, v), hg);
-            unpack(ld_raw<DT, VEC>(sp, v), hp);
-            unpack(ld_raw<DT, VEC>(sm, v), hm);
-#pragma unroll
-            for (int i = 0; i < VEC; ++i)
-                out[v * VEC + i] = (float)(kLn2 * (rec_y(hg[i], hp[i], hm[i], a.c, a.bc) - log2Z));
+// Work item = (sequence, chunk group).  Each wave takes a contiguous run of items, so it
+// repeats the (cheap) ratio test only when it moves on to another sequence; it then streams
+// its chunks of the three recovery rows and stores one mass per chunk.  Waves never wait for
+// or signal each other: the draw itself happens in the next kernel, after the launch boundary
+// has made every mass visible (a device-scope fence per item was measured to cost far more
+// than that launch, because it writes back and invalidates the whole L2 of the XCD).
+template <int DT, int VEC>
+__global__ __launch_bounds__(kRecThreads) void recover_kernel(const RecArgs a) {
+    const int lane = threadIdx.x & 63;
+    const long wave_global = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (kRecThreads / kWave) + (threadIdx.x >> 6)));
+    const long waves_total = (long)gridDim.x * (kRecThreads / kWave);
+    const long items = (long)a.B * a.NG;
+    const long per_wave = (items + waves_total - 1) / waves_total;
+    const long i0 = wave_global * per_wave;
+    const long i1 = min(items, i0 + per_wave);
+    const long nvec = a.V / VEC;
+    const int tailc = a.V - (int)(nvec * VEC);
+    const long nch = (nvec + kWave * kChunkSteps - 1) / (kWave * kChunkSteps);
+
+    int cur_b = -1, n = 0;
+    bool bad = false;
+    for (long i = i0; i < i1; ++i) {
+        const int b = (int)(i / a.NG);
+        const int j = (int)(i - (long)b * a.NG);
+        if (b != cur_b) {
+            // the wave holding group 0 of a sequence is the one that publishes its per-position outputs
+            ratio_test_wave<DT>(a, b, lane, j == 0, n, bad);
+            cur_b = b;
+            if (j == 0 && lane == 0) {
+                a.rec_row[b] = bad ? -1 : n;
+                if (bad) {
+                    a.accepted_len[b] = -1;
+                    a.next_token[b] = -1;
+                    if (a.next_token_logprob) a.next_token_logprob[b] = __int_as_float(0x7FC00000);
+                }
+            }
         }
-        if (tid < tailc) {
-            const long e = nvec * VEC + tid;
-            out[e] = (float)(kLn2 * (rec_y(ld_elem<DT>(g, e), ld_elem<DT>(sp, e), ld_elem<DT>(sm, e), a.c, a.bc) - log2Z));
+        if (bad) continue;
+        const long off = (long)b * a.sb + (long)n * a.st;
+        const void* g = row_ptr<DT>(a.G, off);
+        const void* sp = row_ptr<DT>(a.Sp, off);
+        const void* sm = row_ptr<DT>(a.Sm, off);
+        const int c0 = j * a.CG, c1 = min(a.NC, c0 + a.CG);
+        for (int c = c0; c < c1; ++c) {
+            const Partial p = chunk_mass<DT, VEC>(g, sp, sm, nvec, tailc, nch, c, lane, a.c, a.bc);
+            if (lane == 0) a.mass[(long)b * a.NC + c] = p;
+        }
+    }
+}
+
+// One wave per sequence: the inverse-CDF draw from the chunk masses of the recovery pass.
+template <int DT, int VEC>
+__global__ __launch_bounds__(kRecThreads) void sample_kernel(const RecArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int b = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (kRecThreads / kWave) + (threadIdx.x >> 6)));
+    if (b >= a.B) return;
+    const int n = a.rec_row[b];
+    if (n < 0) return;  // flagged sequence, outputs already written
+    const long nvec = a.V / VEC;
+    const int tailc = a.V - (int)(nvec * VEC);
+    const long nch = (nvec + kWave * kChunkSteps - 1) / (kWave * kChunkSteps);
+    const long off = (long)b * a.sb + (long)n * a.st;
+    sample_wave<DT, VEC>(a, b, n, lane, row_ptr<DT>(a.G, off), row_ptr<DT>(a.Sp, off), row_ptr<DT>(a.Sm, off), nvec,
+                         tailc, nch);
+}
+
+// Optional second sweep: the whole log Softmax(h_rec / T) row of every sequence, same item
+// list as the recovery pass, using the normaliser and row index that pass left behind.
+template <int DT, int VEC>
+__global__ __launch_bounds__(kRecThreads) void logprob_rows_kernel(const RecArgs a) {
+    const int lane = threadIdx.x & 63;
+    const long wave_global = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (kRecThreads / kWave) + (threadIdx.x >> 6)));
+    const long waves_total = (long)gridDim.x * (kRecThreads / kWave);
+    const long items = (long)a.B * a.NG;
+    const long nvec = a.V / VEC;
+    const int tailc = a.V - (int)(nvec * VEC);
+    const long nch = (nvec + kWave * kChunkSteps - 1) / (kWave * kChunkSteps);
+    for (long i = wave_global; i < items; i += waves_total) {
+        const int b = (int)(i / a.NG);
+        const int j = (int)(i - (long)b * a.NG);
+        const int n = a.rec_row[b];
+        if (n < 0) continue;  // flagged sequence: row left unwritten
+        const double log2Z = a.log2Z[b];
+        const long off = (long)b * a.sb + (long)n * a.st;
+        const void* g = row_ptr<DT>(a.G, off);
+        const void* sp = row_ptr<DT>(a.Sp, off);
+        const void* sm = row_ptr<DT>(a.Sm, off);
+        float* out = a.recovery_logprobs + (long)b * a.V;
+        const int c0 = j * a.CG, c1 = min(a.NC, c0 + a.CG);
+        for (int c = c0; c < c1; ++c) {
+            const int nsteps = (c < nch) ? kChunkSteps : 1;
+            for (int s = 0; s < nsteps; ++s) {
+                double y[VEC];
+                long first;
+                const int cnt = chunk_lane_y<DT, VEC>(g, sp, sm, nvec, tailc, nch, c, s, lane, a.c, a.bc, y, first);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e)
+                    if (e < cnt) out[first + e] = (float)(kLn2 * (y[e] - log2Z));
+            }
         }
     }
 }
@@ -629,7 +841,8 @@ struct Plan {
     int vecfast;     // logits per 16-byte vector
     int NS;          // slices per row
     int slice_vecs;  // fast-width vectors per slice
-    size_t off_partial;
+    int NCmax;       // upper bound of recovery chunks per row (element-wise path)
+    size_t off_log2z, off_recrow, off_mass, off_partial;
     size_t bytes;
 };
 
@@ -644,14 +857,20 @@ bool shape_ok(const ss_params* p) {
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// Slices per row: 32 KiB slices for big batches, smaller ones (down to one unrolled group)
+int chunks_per_row(int V, int vec) {
+    const long nvec = V / vec;
+    const long nch = (nvec + kWave * kChunkSteps - 1) / (kWave * kChunkSteps);
+    return (int)nch + ((V % vec) ? 1 : 0);
+}
+
+// Slices per row: 64 KiB slices for big batches, smaller ones (down to one unrolled group)
 // when there are too few rows to give every resident wave several slices.
 Plan make_plan(const ss_params* p) {
     Plan pl;
     pl.vecfast = p->dtype == SS_BF16 ? 8 : 4;
     const long nvec = (p->vocab + pl.vecfast - 1) / pl.vecfast;
     const long rows2 = (long)p->batch * p->k_max * 2;
-    long ns_lo = (nvec + kMaxSliceVecs - 1) / kMaxSliceVecs;
+    long ns_lo = (nvec + tune_slice_max() - 1) / tune_slice_max();
     long ns_hi = (nvec + kMinSliceVecs - 1) / kMinSliceVecs;
     long want = rows2 > 0 ? (32768 + rows2 - 1) / rows2 : 1;
     long ns = want < ns_lo ? ns_lo : (want > ns_hi ? ns_hi : want);
@@ -663,8 +882,14 @@ Plan make_plan(const ss_params* p) {
     if (ns < 1) ns = 1;
     pl.NS = (int)ns;
     pl.slice_vecs = (int)sv;
-    pl.off_partial = align_up(((size_t)p->batch + 1) * sizeof(int32_t), 256);
-    pl.bytes = pl.off_partial + align_up((size_t)(rows2 > 0 ? rows2 : 1) * pl.NS * sizeof(Partial), 256);
+    pl.NCmax = chunks_per_row(p->vocab, 1);  // the element-wise path has the most chunks
+    const size_t B = (size_t)p->batch;
+    size_t o = align_up((B + 1) * sizeof(int32_t), 256);           // row_off
+    pl.off_log2z = o;   o += align_up((B ? B : 1) * sizeof(double), 256);
+    pl.off_recrow = o;  o += align_up((B ? B : 1) * sizeof(int32_t), 256);
+    pl.off_mass = o;    o += align_up((B ? B : 1) * (size_t)pl.NCmax * sizeof(Partial), 256);
+    pl.off_partial = o; o += align_up((size_t)(rows2 > 0 ? rows2 : 1) * pl.NS * sizeof(Partial), 256);
+    pl.bytes = o;
     return pl;
 }
 
@@ -681,29 +906,49 @@ int device_cu_count() {
 }
 
 template <int DT, int VEC, int VECFAST>
-hipError_t launch_all(const LseArgs& la, const RecArgs& ra, const int32_t* draft_len, int32_t* row_off,
-                      hipStream_t stream, hipEvent_t* ev) {
+hipError_t launch_all(LseArgs la, RecArgs ra, hipStream_t stream, hipEvent_t* ev) {
     const int B = ra.B, kmax = ra.kmax, V = ra.V;
+    const int cus = device_cu_count();
+    const bool ragged = ra.draft_len != nullptr && kmax > 0;
+    // the row list is built in LDS by the row pass unless the batch is too large for it
+    const bool global_list = ragged && B > kMaxLdsBatch;
+    la.draft_len = ragged ? ra.draft_len : nullptr;
+    la.list_in_lds = (ragged && !global_list) ? 1 : 0;
     if (ev) hipEventRecord(ev[0], stream);
-    if (draft_len && kmax > 0)
-        hipLaunchKernelGGL(prep_rows_kernel, dim3(1), dim3(1024), 0, stream, draft_len, B, kmax, row_off);
+    if (global_list)
+        hipLaunchKernelGGL(prep_rows_kernel, dim3(1), dim3(1024), 0, stream, ra.draft_len, B, kmax, la.row_off);
     if (ev) hipEventRecord(ev[1], stream);
     const long items = (long)B * kmax * 2 * la.NS;
-    if (items > 0) {
+    if (items > 0) {  // row pass
         const long per_wg = kLseThreads / kWave;
         long wgs = (items + per_wg - 1) / per_wg;
-        const long cap = (long)device_cu_count() * 8;
+        const long cap = (long)cus * tune_wg_per_cu();
         if (wgs > cap) wgs = cap;
-        hipLaunchKernelGGL((row_lse_kernel<DT, VEC, VECFAST>), dim3((unsigned)wgs), dim3(kLseThreads), 0, stream, la);
+        const size_t lds = la.list_in_lds ? (size_t)(B + 1) * sizeof(int) : 0;
+        switch (tune_unroll()) {
+            case 8: hipLaunchKernelGGL((row_lse_kernel<DT, VEC, VECFAST, 8>), dim3((unsigned)wgs), dim3(kLseThreads), lds, stream, la); break;
+            default: hipLaunchKernelGGL((row_lse_kernel<DT, VEC, VECFAST, 4>), dim3((unsigned)wgs), dim3(kLseThreads), lds, stream, la); break;
+        }
     }
     if (ev) hipEventRecord(ev[2], stream);
-    const long nvec = V / VEC;
-    const long nch = (nvec + kWave * kChunkSteps - 1) / (kWave * kChunkSteps);
-    const size_t smem = (size_t)(nch + 1) * 8;
-    // a long row is worth a full 16-wave workgroup; many sequences fill the chip either way
-    const int nt = 1024;
-    hipLaunchKernelGGL((accept_recover_kernel<DT, VEC>), dim3((unsigned)B), dim3(nt), smem, stream, ra);
+    // recovery pass: enough chunk groups per sequence to give every resident wave a few items
+    ra.NC = chunks_per_row(V, VEC);
+    const long waves = (long)cus * tune_rec_wg_per_cu() * (kRecThreads / kWave);
+    long ng = (4 * waves + B - 1) / B;
+    if (ng > ra.NC) ng = ra.NC;
+    if (ng < 1) ng = 1;
+    ra.CG = (int)((ra.NC + ng - 1) / ng);
+    ra.NG = (ra.NC + ra.CG - 1) / ra.CG;
+    const long ritems = (long)B * ra.NG;
+    long rwgs = (ritems + (kRecThreads / kWave) - 1) / (kRecThreads / kWave);
+    if (rwgs > (long)cus * tune_rec_wg_per_cu()) rwgs = (long)cus * tune_rec_wg_per_cu();
+    hipLaunchKernelGGL((recover_kernel<DT, VEC>), dim3((unsigned)rwgs), dim3(kRecThreads), 0, stream, ra);
+    const int swgs = (B + (kRecThreads / kWave) - 1) / (kRecThreads / kWave);
+    hipLaunchKernelGGL((sample_kernel<DT, VEC>), dim3((unsigned)swgs), dim3(kRecThreads), 0, stream, ra);
     if (ev) hipEventRecord(ev[3], stream);
+    if (ra.recovery_logprobs)
+        hipLaunchKernelGGL((logprob_rows_kernel<DT, VEC>), dim3((unsigned)rwgs), dim3(kRecThreads), 0, stream, ra);
+    if (ev) hipEventRecord(ev[4], stream);
     return hipGetLastError();
 }
 
@@ -711,7 +956,66 @@ ss_status verify_block_impl(const void* G, const void* S_ctx, const void* S_noct
                             const int32_t* draft_len, const float* uniforms, const ss_params* params,
                             int32_t* accepted_len, int32_t* next_token, float* next_token_logprob,
                             float* recovery_logprobs, float* draft_logprobs, void* workspace,
-                            size_t workspace_bytes, void* stream, hipEvent_t* ev);
+                            size_t workspace_bytes, void* stream, hipEvent_t* ev) {
+    if (!params) return SS_ERR_NULL;
+    if (params->dtype != SS_F32 && params->dtype != SS_BF16) return SS_ERR_DTYPE;
+    if (!shape_ok(params)) return SS_ERR_SHAPE;
+    if (!G || !S_ctx || !S_noctx || !uniforms || !accepted_len || !next_token) return SS_ERR_NULL;
+    if (params->k_max > 0 && !draft) return SS_ERR_NULL;
+    if (!(params->lambda > 0.f) || !std::isfinite(params->lambda)) return SS_ERR_PARAM;
+    if (!(params->temperature > 0.f) || !std::isfinite(params->temperature)) return SS_ERR_PARAM;
+    if (!std::isfinite(params->beta)) return SS_ERR_PARAM;
+    if (params->flags != 0) return SS_ERR_PARAM;
+    const long V = params->vocab;
+    if (params->stride_t < 0 || params->stride_b < 0) return SS_ERR_STRIDE;
+    const long st = params->stride_t ? params->stride_t : V;
+    const long sb = params->stride_b ? params->stride_b : (long)(params->k_max + 1) * st;
+    if (st < V || sb < (long)params->k_max * st + V) return SS_ERR_STRIDE;
+    const Plan pl = make_plan(params);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 || workspace_bytes < pl.bytes)
+        return SS_ERR_WORKSPACE;
+    if (params->batch == 0) return SS_OK;
+
+    const int esz = params->dtype == SS_BF16 ? 2 : 4;
+    const bool fast = ((reinterpret_cast<uintptr_t>(G) | reinterpret_cast<uintptr_t>(S_ctx) |
+                        reinterpret_cast<uintptr_t>(S_noctx)) & 15) == 0 &&
+                      (st * esz) % 16 == 0 && (sb * esz) % 16 == 0;
+
+    char* ws = static_cast<char*>(workspace);
+
+    // c = log2(e)/T as an unevaluated sum of two floats for the fp32 row pass
+    const double T = (double)params->temperature;
+    const double c = kLog2e / T;
+    const float c_hi = (float)c;
+    const float c_lo = (float)(c - (double)c_hi);
+
+    LseArgs la;
+    la.G = G; la.Sm = S_noctx; la.draft_len = draft_len; la.row_off = reinterpret_cast<int32_t*>(ws);
+    la.partial = reinterpret_cast<Partial*>(ws + pl.off_partial);
+    la.sb = sb; la.st = st; la.B = params->batch; la.kmax = params->k_max; la.V = params->vocab;
+    la.NS = pl.NS; la.slice_vecs = pl.slice_vecs; la.list_in_lds = 0; la.c_hi = c_hi; la.c_lo = c_lo;
+
+    RecArgs ra;
+    ra.G = G; ra.Sp = S_ctx; ra.Sm = S_noctx; ra.draft = draft; ra.draft_len = draft_len; ra.uniforms = uniforms;
+    ra.row_off = la.row_off; ra.partial = la.partial;
+    ra.mass = reinterpret_cast<Partial*>(ws + pl.off_mass);
+    ra.log2Z = reinterpret_cast<double*>(ws + pl.off_log2z);
+    ra.rec_row = reinterpret_cast<int32_t*>(ws + pl.off_recrow);
+    ra.accepted_len = accepted_len; ra.next_token = next_token;
+    ra.next_token_logprob = next_token_logprob; ra.recovery_logprobs = recovery_logprobs;
+    ra.draft_logprobs = draft_logprobs; ra.sb = sb; ra.st = st; ra.B = params->batch; ra.kmax = params->k_max;
+    ra.V = params->vocab; ra.NS = pl.NS; ra.NC = 0; ra.NG = 1; ra.CG = 1; ra.c = c;
+    ra.bc = (double)params->beta * c; ra.ln_lambda = std::log((double)params->lambda);
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t err;
+    if (params->dtype == SS_BF16) {
+        err = fast ? launch_all<SS_BF16, 8, 8>(la, ra, s, ev) : launch_all<SS_BF16, 1, 8>(la, ra, s, ev);
+    } else {
+        err = fast ? launch_all<SS_F32, 4, 4>(la, ra, s, ev) : launch_all<SS_F32, 1, 4>(la, ra, s, ev);
+    }
+    return err == hipSuccess ? SS_OK : SS_ERR_DEVICE;
+}
 
 }  // namespace
 
@@ -757,79 +1061,6 @@ ss_status specsteer_verify_block_timed(const void* G, const void* S_ctx, const v
     for (int i = 0; i < made; ++i) hipEventDestroy(ev[i]);
     return st;
 }
-
-}  // extern "C"
-
-namespace {
-
-ss_status verify_block_impl(const void* G, const void* S_ctx, const void* S_noctx, const int32_t* draft,
-                            const int32_t* draft_len, const float* uniforms, const ss_params* params,
-                            int32_t* accepted_len, int32_t* next_token, float* next_token_logprob,
-                            float* recovery_logprobs, float* draft_logprobs, void* workspace,
-                            size_t workspace_bytes, void* stream, hipEvent_t* ev) {
-    if (!params) return SS_ERR_NULL;
-    if (params->dtype != SS_F32 && params->dtype != SS_BF16) return SS_ERR_DTYPE;
-    if (!shape_ok(params)) return SS_ERR_SHAPE;
-    if (!G || !S_ctx || !S_noctx || !uniforms || !accepted_len || !next_token) return SS_ERR_NULL;
-    if (params->k_max > 0 && !draft) return SS_ERR_NULL;
-    if (!(params->lambda > 0.f) || !std::isfinite(params->lambda)) return SS_ERR_PARAM;
-    if (!(params->temperature > 0.f) || !std::isfinite(params->temperature)) return SS_ERR_PARAM;
-    if (!std::isfinite(params->beta)) return SS_ERR_PARAM;
-    if (params->flags != 0) return SS_ERR_PARAM;
-    const long V = params->vocab;
-    if (params->stride_t < 0 || params->stride_b < 0) return SS_ERR_STRIDE;
-    const long st = params->stride_t ? params->stride_t : V;
-    const long sb = params->stride_b ? params->stride_b : (long)(params->k_max + 1) * st;
-    if (st < V || sb < (long)params->k_max * st + V) return SS_ERR_STRIDE;
-    const Plan pl = make_plan(params);
-    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 || workspace_bytes < pl.bytes)
-        return SS_ERR_WORKSPACE;
-    if (params->batch == 0) return SS_OK;
-
-    const int esz = params->dtype == SS_BF16 ? 2 : 4;
-    const bool fast = ((reinterpret_cast<uintptr_t>(G) | reinterpret_cast<uintptr_t>(S_ctx) |
-                        reinterpret_cast<uintptr_t>(S_noctx)) & 15) == 0 &&
-                      (st * esz) % 16 == 0 && (sb * esz) % 16 == 0;
-
-    char* ws = static_cast<char*>(workspace);
-    int32_t* row_off = reinterpret_cast<int32_t*>(ws);
-    Partial* partial = reinterpret_cast<Partial*>(ws + pl.off_partial);
-    const bool ragged = draft_len != nullptr && params->k_max > 0;
-
-    // c = log2(e)/T as an unevaluated sum of two floats for the fp32 row pass
-    const double T = (double)params->temperature;
-    const double c = kLog2e / T;
-    const float c_hi = (float)c;
-    const float c_lo = (float)(c - (double)c_hi);
-
-    LseArgs la;
-    la.G = G; la.Sm = S_noctx; la.row_off = ragged ? row_off : nullptr; la.partial = partial;
-    la.sb = sb; la.st = st; la.B = params->batch; la.kmax = params->k_max; la.V = params->vocab;
-    la.NS = pl.NS; la.slice_vecs = pl.slice_vecs; la.c_hi = c_hi; la.c_lo = c_lo;
-
-    RecArgs ra;
-    ra.G = G; ra.Sp = S_ctx; ra.Sm = S_noctx; ra.draft = draft; ra.draft_len = draft_len; ra.uniforms = uniforms;
-    ra.row_off = la.row_off; ra.partial = partial; ra.accepted_len = accepted_len; ra.next_token = next_token;
-    ra.next_token_logprob = next_token_logprob; ra.recovery_logprobs = recovery_logprobs;
-    ra.draft_logprobs = draft_logprobs; ra.sb = sb; ra.st = st; ra.B = params->batch; ra.kmax = params->k_max;
-    ra.V = params->vocab; ra.NS = pl.NS; ra.c = c; ra.bc = (double)params->beta * c;
-    ra.ln_lambda = std::log((double)params->lambda);
-
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t err;
-    if (params->dtype == SS_BF16) {
-        err = fast ? launch_all<SS_BF16, 8, 8>(la, ra, draft_len, row_off, s, ev)
-                   : launch_all<SS_BF16, 1, 8>(la, ra, draft_len, row_off, s, ev);
-    } else {
-        err = fast ? launch_all<SS_F32, 4, 4>(la, ra, draft_len, row_off, s, ev)
-                   : launch_all<SS_F32, 1, 4>(la, ra, draft_len, row_off, s, ev);
-    }
-    return err == hipSuccess ? SS_OK : SS_ERR_DEVICE;
-}
-
-}  // namespace
-
-extern "C" {
 
 const char* specsteer_status_string(int status) {
     switch (status) {
