@@ -130,15 +130,14 @@ ss_status specsteer_verify_block(const void *G, const void *S_ctx, const void *S
  * milliseconds of each stage to the host array stage_ms[SS_NUM_STAGES]:
  *   [SS_STAGE_PREP]    ragged row list (0 when draft_len is NULL),
  *   [SS_STAGE_ROW_LSE] the log-sum-exp pass over every valid row of G and S_noctx,
- *   [SS_STAGE_RECOVER] ratio test, first rejection, recovery distribution and sampling,
- *   [SS_STAGE_LOGPROBS] the optional full recovery log-prob rows (0 when not requested).
+ *   [SS_STAGE_RECOVER] ratio test, first rejection, recovery distribution, sampling and the
+ *                      optional log-prob rows.
  * Creates and destroys its events inside the call, so it is not for latency-critical use.
  */
 #define SS_STAGE_PREP 0
 #define SS_STAGE_ROW_LSE 1
 #define SS_STAGE_RECOVER 2
-#define SS_STAGE_LOGPROBS 3
-#define SS_NUM_STAGES 4
+#define SS_NUM_STAGES 3
 ss_status specsteer_verify_block_timed(const void *G, const void *S_ctx, const void *S_noctx,
                                        const int32_t *draft, const int32_t *draft_len,
                                        const float *uniforms, const ss_params *params,

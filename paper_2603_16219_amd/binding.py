@@ -89,7 +89,7 @@ def _ptr(t: Optional[torch.Tensor]):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
-STAGES = ("prep", "row_lse", "recover", "logprob_rows")
+STAGES = ("prep", "row_lse", "recover")
 
 
 def verify_block_raw(G, S_ctx, S_noctx, draft, draft_len, uniforms, params: SSParams, accepted_len,

@@ -3,25 +3,26 @@
 // What is computed (Algorithm 1 phases 2-3, Eq. 7, Eq. 8) is stated in
 // include/specsteer.h.  How it is computed here:
 //
-//   prep_rows      (ragged batches only) exclusive scan of the draft lengths, so the
-//                  valid (sequence, position) rows form one dense list.
 //   row_lse        the dominant, HBM-bound pass.  Every valid row of G and S_noctx is
 //                  cut into slices; one 64-lane wavefront streams one slice with
-//                  16-byte loads and keeps a per-lane running (E, s) with
+//                  non-temporal 16-byte loads and keeps a per-lane running (E, s) with
 //                  sum_v 2^(h_v*c - E) = s,  c = log2(e)/T,  E an integer >= max(h*c).
 //                  An integer reference makes every rescale an exact ldexp and costs
 //                  no extra exponential: one v_exp_f32 per logit.  Waves never
-//                  synchronise with each other (no LDS, no barrier); a persistent grid
-//                  strides over the slice list.
-//   accept_recover one workgroup per sequence.  Wave 0 combines the slice partials in
-//                  double, gathers the two draft-token logits per position, applies the
-//                  ratio test and finds the first rejection with a wave ballot.  All
-//                  waves then stream the three logit rows of the rejected (or bonus)
-//                  position once, forming h_rec in double, and record one (E, s) mass per
-//                  2048-logit chunk in LDS.  A double-precision scan over the chunk
-//                  masses locates the chunk holding u*Z; only that chunk is read again
-//                  to pick the token.  The full log-prob row is a second sweep, taken
-//                  only when the caller asks for it.
+//                  synchronise with each other (no barrier in the loop); a persistent
+//                  grid strides over the slice list.  A ragged batch's row list is an
+//                  exclusive scan of the draft lengths that every workgroup rebuilds in
+//                  LDS at kernel start (prep_rows does it once in global memory for
+//                  batches too large for LDS).
+//   accept_recover one 16-wave workgroup per sequence.  Each (position, tensor) pair
+//                  gets a wave that merges the slice partials and gathers the draft
+//                  token's logit; wave 0 applies the ratio test and finds the first
+//                  rejection with a ballot.  All waves then stream the three logit rows
+//                  of the rejected (or bonus) position once, forming the recovery
+//                  exponent in double, and record one (E, s) mass per 2048-logit chunk
+//                  in LDS.  A double-precision scan over the chunk masses locates the
+//                  chunk holding u*Z; only that chunk is read again to pick the token.
+//                  The full log-prob row is a second sweep, taken only on request.
 //
 // Precision: logits are widened exactly; sums of exponentials are accumulated in
 // fp32 (one rounding per term, pairwise across lanes), every per-row scalar
@@ -30,7 +31,6 @@
 
 #include <cmath>
 #include <cstdint>
-#include <cstdlib>
 
 #include "specsteer.h"
 
@@ -38,9 +38,9 @@ namespace {
 
 constexpr int kWave = 64;
 constexpr int kLseThreads = 256;            // 4 independent waves per workgroup
-constexpr int kLseUnrollMin = 4;            // 16-byte loads in flight per lane
-constexpr int kLseWgPerCu = 4;              // persistent workgroups per CU: 8 waves/CU read fastest
-constexpr int kMinSliceVecs = kWave * kLseUnrollMin;  // smallest slice: one unrolled group
+constexpr int kLseUnroll = 4;               // 16-byte loads in flight per lane
+constexpr int kLseWgPerCu = 4;              // persistent workgroups per CU (16 waves/CU measured fastest)
+constexpr int kMinSliceVecs = kWave * kLseUnroll;  // smallest slice: one unrolled group
 constexpr int kMaxSliceVecs = 4096;         // 64 KiB of logits per slice
 constexpr int kMaxSlices = 64;
 constexpr int kMaxLdsBatch = 8192;          // ragged batches up to this size keep their row list in LDS
@@ -50,19 +50,7 @@ constexpr float kEClamp = 5.0e8f;           // keeps (int)ceil(h*c) inside int32
 constexpr double kLn2 = 0.693147180559945309417232121458;
 constexpr double kLog2e = 1.442695040888963407359924681002;
 
-constexpr int kRecThreads = 256;            // recovery pass: 4 independent waves per workgroup
-constexpr int kRecWgPerCu = 4;
-
-// TEMPORARY tuning knobs (environment), removed once the values are fixed.
-inline int env_int(const char* name, int dflt) {
-    const char* e = getenv(name);
-    const int v = e ? atoi(e) : dflt;
-    return v < 1 ? dflt : v;
-}
-inline int tune_wg_per_cu() { static int v = env_int("SS_TUNE_WG", kLseWgPerCu); return v; }
-inline int tune_unroll() { static int v = env_int("SS_TUNE_U", 4); return v; }
-inline int tune_slice_max() { static int v = env_int("SS_TUNE_SLICE", kMaxSliceVecs); return v < kMinSliceVecs ? kMinSliceVecs : v; }
-inline int tune_rec_wg_per_cu() { static int v = env_int("SS_TUNE_RWG", kRecWgPerCu); return v; }
+constexpr int kRecThreads = 1024;           // accept + recover: one 16-wave workgroup per sequence
 
 struct Partial {
     int E;    // integer exponent reference of this slice
@@ -328,7 +316,7 @@ struct LseArgs {
 // strides over the item list.  Ragged batches build the row list in LDS at kernel start
 // (every workgroup repeats the same small scan), so no separate launch is needed.
 // Workgroup 0 also publishes the row list for the recovery pass.
-template <int DT, int VEC, int VECFAST, int kLseUnroll>
+template <int DT, int VEC, int VECFAST, int kUnroll>
 __global__ __launch_bounds__(kLseThreads) void row_lse_kernel(const LseArgs a) {
     extern __shared__ int lds_off[];
     const int lane = threadIdx.x & 63;
@@ -348,7 +336,7 @@ __global__ __launch_bounds__(kLseThreads) void row_lse_kernel(const LseArgs a) {
     const long slice_units = (long)a.slice_vecs * (VECFAST / VEC);
     const long nvec = a.V / VEC;
     const int tailc = a.V - (int)(nvec * VEC);
-    constexpr long kGroup = (long)kWave * kLseUnroll;
+    constexpr long kGroup = (long)kWave * kUnroll;
 
     for (long item = wave_global; item < items; item += waves_total) {
         const int k = (int)(item % a.NS);
@@ -376,18 +364,18 @@ __global__ __launch_bounds__(kLseThreads) void row_lse_kernel(const LseArgs a) {
         Acc acc{kEInit, 0.f};
         long v = v0 + lane;
         for (long g = 0; g < nfull; ++g, v += kGroup) {
-            typename RawT<DT, VEC>::type raw[kLseUnroll];
+            typename RawT<DT, VEC>::type raw[kUnroll];
 #pragma unroll
-            for (int j = 0; j < kLseUnroll; ++j) raw[j] = ld_raw<DT, VEC>(row, v + (long)kWave * j);
-            float h[kLseUnroll * VEC];
+            for (int j = 0; j < kUnroll; ++j) raw[j] = ld_raw<DT, VEC>(row, v + (long)kWave * j);
+            float h[kUnroll * VEC];
 #pragma unroll
-            for (int j = 0; j < kLseUnroll; ++j) {
+            for (int j = 0; j < kUnroll; ++j) {
                 float hj[VEC];
                 unpack(raw[j], hj);
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) h[j * VEC + i] = hj[i];
             }
-            acc_add_f32<kLseUnroll * VEC>(acc, h, a.c_hi, a.c_lo);
+            acc_add_f32<kUnroll * VEC>(acc, h, a.c_hi, a.c_lo);
         }
         for (; v < v1; v += kWave) {
             float hj[VEC];
@@ -414,9 +402,6 @@ struct RecArgs {
     const float* uniforms;
     const int32_t* row_off;  // ragged: [B+1] row list written by the row pass
     const Partial* partial;  // [rows][2][NS] from the row pass
-    Partial* mass;           // [B][NC] one (E, s) per recovery chunk
-    double* log2Z;           // [B] log2 of the recovery normaliser (for the log-prob sweep)
-    int32_t* rec_row;        // [B] recovery row n_b, or -1 for a flagged sequence
     int32_t* accepted_len;
     int32_t* next_token;
     float* next_token_logprob;
@@ -425,119 +410,66 @@ struct RecArgs {
     long sb, st;
     int B, kmax, V, NS;
     int NC;          // chunks per row (full chunks + one pseudo-chunk for the logits past the last vector)
-    int NG, CG;      // chunk groups per row, chunks per group
     double c;        // log2(e) / T
     double bc;       // beta * log2(e) / T
     double ln_lambda;
 };
 
-// log2 of sum_v 2^(h_v * c) for one row, from its slice partials.  Partials are fetched eight
-// at a time (one memory round trip per batch) and merged online in double.
-__device__ __forceinline__ double combine_partials(const Partial* p, int NS) {
-    int Em = kEInit;
-    double S = 0.0;
-    for (int k0 = 0; k0 < NS; k0 += 8) {
-        Partial q[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            q[j] = Partial{kEInit, 0.f};
-            if (k0 + j < NS) q[j] = p[k0 + j];
-        }
-        int Eb = q[0].E;
-#pragma unroll
-        for (int j = 1; j < 8; ++j) Eb = max(Eb, q[j].E);
-        if (Eb > Em) {
-            S = ldexp(S, Em - Eb);
-            Em = Eb;
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) S += ldexp((double)q[j].s, q[j].E - Em);
+// log2 of sum_v 2^(h_v * c) for one row from its slice partials, by one wave: lane k holds
+// slice k (one coalesced load for up to 64 slices), the merge is two DPP reductions.
+__device__ __forceinline__ double combine_partials_wave(const Partial* p, int NS, int lane) {
+    Acc q{kEInit, 0.f};
+    if (lane < NS) {
+        const Partial v = p[lane];
+        q.E = v.E;
+        q.s = v.s;
     }
-    return (double)Em + log2(S);
+    const Partial m = wave_combine(q);
+    return (double)m.E + log2((double)m.s);
 }
 
-// Phase 2 for one sequence, by one wave (lane = drafted position, 64 at a time): the ratio test
-// of Eq. 7 at every position and the first rejection by ballot.  Wave-uniform results.
-// With `publish` the wave also writes this sequence's draft log-probs.
-template <int DT>
-__device__ __forceinline__ void ratio_test_wave(const RecArgs& a, int b, int lane, bool publish, int& n, bool& bad) {
-    const int kmax = a.kmax, V = a.V;
-    // everything whose address does not depend on other loads is requested first, so the whole
-    // test costs two memory round trips: (length, row offset, draft ids, uniforms), then
-    // (slice partials, draft-token logits)
-    int y_first = -1;
-    float u_first = 0.f;
-    if (lane < kmax) {
-        y_first = a.draft[(long)b * kmax + lane];
-        u_first = a.uniforms[(long)b * (kmax + 1) + lane];
-    }
-    const int K = a.draft_len ? a.draft_len[b] : kmax;
-    const bool bad_len = (K < 0 || K > kmax);
-    int first_rej = bad_len ? 0 : K;
-    bool any_bad = bad_len;
-    const long r0 = (a.draft_len && kmax > 0) ? (long)a.row_off[b] : (long)b * kmax;
-    for (int t0 = 0; !bad_len && t0 < K; t0 += kWave) {
-        const int t = t0 + lane;
-        bool rej = false, oob = false;
-        if (t < K) {
-            const int y = t0 == 0 ? y_first : a.draft[(long)b * kmax + t];
-            const float u = t0 == 0 ? u_first : a.uniforms[(long)b * (kmax + 1) + t];
-            if (y < 0 || y >= V) {
-                oob = true;
-            } else {
-                const Partial* p = a.partial + (r0 + t) * 2 * a.NS;
-                const double LG = combine_partials(p, a.NS);
-                const double LS = combine_partials(p + a.NS, a.NS);
-                const long off = (long)b * a.sb + (long)t * a.st;
-                const double hG = (double)ld_elem<DT>(row_ptr<DT>(a.G, off), y);
-                const double hS = (double)ld_elem<DT>(row_ptr<DT>(a.Sm, off), y);
-                const double lpG = kLn2 * (hG * a.c - LG);  // log P_LLM(y_t)
-                const double lpS = kLn2 * (hS * a.c - LS);  // log P_SLM^-(y_t)
-                const double alpha = fmin(1.0, exp(lpG - lpS - a.ln_lambda));  // Eq. 7
-                rej = !((double)u <= alpha);
-                if (publish && a.draft_logprobs) {
-                    a.draft_logprobs[((long)b * kmax + t) * 2 + 0] = (float)lpG;
-                    a.draft_logprobs[((long)b * kmax + t) * 2 + 1] = (float)lpS;
-                }
-            }
-        }
-        any_bad = any_bad || (__ballot(oob) != 0ull);
-        const unsigned long long rmask = __ballot(rej);
-        if (rmask && first_rej == K) first_rej = t0 + first_lane(rmask);
-    }
-    n = first_rej;
-    bad = any_bad;
-    if (publish && a.draft_logprobs) {  // padded slots read 0, a flagged sequence reads NaN throughout
-        const int from = bad ? 0 : K;
-        const float fill = bad ? __int_as_float(0x7FC00000) : 0.f;
-        for (int i = from * 2 + lane; i < kmax * 2; i += kWave) a.draft_logprobs[(long)b * kmax * 2 + i] = fill;
-    }
-}
-
-// The logits one lane owns in step j of chunk c, as recovery exponents y.  Regular chunks hold
-// kChunkSteps wave-steps of full vectors; the pseudo-chunk c == nch holds the < VEC logits
-// past the last full vector, one per lane.  Returns how many entries of y are valid and the
-// vocabulary index of the first.
+// Probability terms 2^(y - E*) of the logits one lane owns in recovery chunk c, laid out so that
+// a lane's logits are consecutive in the vocabulary: lane l holds vectors 4l..4l+3 of the chunk.
+// The pseudo-chunk c == nch holds the < VEC logits past the last full vector, one per lane.
+// cnt[j] says how many entries of p[j] are valid; first[j] is the vocabulary index of p[j][0].
 template <int DT, int VEC>
-__device__ __forceinline__ int chunk_lane_y(const void* g, const void* sp, const void* sm, long nvec, int tailc,
-                                            long nch, long c, int j, int lane, double cc, double bc,
-                                            double (&y)[VEC], long& first) {
-    if (c < nch) {
-        const long v = c * (long)(kWave * kChunkSteps) + (long)j * kWave + lane;
-        first = v * VEC;
-        if (v >= nvec) return 0;
-        float hg[VEC], hp[VEC], hm[VEC];
-        unpack(ld_raw<DT, VEC>(g, v), hg);
-        unpack(ld_raw<DT, VEC>(sp, v), hp);
-        unpack(ld_raw<DT, VEC>(sm, v), hm);
+__device__ __forceinline__ void chunk_lane_terms(const void* g, const void* sp, const void* sm, long nvec, int tailc,
+                                                 long nch, long c, int lane, double cc, double bc, double dE,
+                                                 float (&p)[kChunkSteps][VEC], long (&first)[kChunkSteps],
+                                                 int (&cnt)[kChunkSteps]) {
+    typename RawT<DT, VEC>::type rg[kChunkSteps], rp[kChunkSteps], rm[kChunkSteps];
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) y[i] = rec_y(hg[i], hp[i], hm[i], cc, bc);
-        return VEC;
+    for (int j = 0; j < kChunkSteps; ++j) {
+        const long v = c * (long)(kWave * kChunkSteps) + (long)lane * kChunkSteps + j;
+        cnt[j] = 0;
+        first[j] = v * VEC;
+        if (c < nch && v < nvec) {
+            rg[j] = ld_raw<DT, VEC>(g, v);
+            rp[j] = ld_raw<DT, VEC>(sp, v);
+            rm[j] = ld_raw<DT, VEC>(sm, v);
+            cnt[j] = VEC;
+        }
     }
-    first = nvec * VEC + lane;
-    if (j > 0 || lane >= tailc) return 0;
-    y[0] = rec_y(ld_elem<DT>(g, first), ld_elem<DT>(sp, first), ld_elem<DT>(sm, first), cc, bc);
-    return 1;
+#pragma unroll
+    for (int j = 0; j < kChunkSteps; ++j) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) p[j][i] = 0.f;
+        if (cnt[j]) {
+            float hg[VEC], hp[VEC], hm[VEC];
+            unpack(rg[j], hg);
+            unpack(rp[j], hp);
+            unpack(rm[j], hm);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i)
+                p[j][i] = __builtin_amdgcn_exp2f((float)(rec_y(hg[i], hp[i], hm[i], cc, bc) - dE));
+        }
+    }
+    if (c >= nch && lane < tailc) {
+        first[0] = nvec * VEC + lane;
+        cnt[0] = 1;
+        p[0][0] = __builtin_amdgcn_exp2f(
+            (float)(rec_y(ld_elem<DT>(g, first[0]), ld_elem<DT>(sp, first[0]), ld_elem<DT>(sm, first[0]), cc, bc) - dE));
+    }
 }
 
 // (E, s) mass of recovery chunk c, by one wave: sum over the chunk of 2^(y - E).
@@ -577,42 +509,23 @@ __device__ __forceinline__ Partial chunk_mass(const void* g, const void* sp, con
     return wave_combine(acc);
 }
 
-// Inverse-CDF draw for one sequence by one wave, once every chunk mass of its recovery row is
-// known: a double-precision scan over the chunk masses finds the chunk holding u*Z, and only
-// that chunk is read again to pick the token.
+// Inverse-CDF draw for one sequence by one wave, from the chunk masses `tab` (LDS) of its
+// recovery row: a double-precision scan over the masses finds the chunk holding u*Z, and only
+// that chunk is read again to pick the token.  Returns log2 Z; writes the per-sequence outputs.
 template <int DT, int VEC>
-__device__ __forceinline__ void sample_wave(const RecArgs& a, int b, int n, int lane, const void* g, const void* sp,
-                                            const void* sm, long nvec, int tailc, long nch) {
+__device__ __forceinline__ double sample_wave(const RecArgs& a, int b, int n, int lane, const Partial* tab,
+                                              const void* g, const void* sp, const void* sm, long nvec, int tailc,
+                                              long nch) {
     const int NC = a.NC;
-    const Partial* tab = a.mass + (long)b * NC;
-    const double us = (double)a.uniforms[(long)b * (a.kmax + 1) + a.kmax];  // issued with the first table loads
-    // Each lane owns a contiguous run of `per` chunks.  Up to kTabRegs per lane (any realistic
-    // vocabulary) they are fetched into registers in one round trip; longer runs re-read memory.
-    constexpr int kTabRegs = 4;
+    const double us = (double)a.uniforms[(long)b * (a.kmax + 1) + a.kmax];
+    // each lane owns a contiguous run of `per` chunks
     const int per = (NC + kWave - 1) / kWave;
     const int lo = min(lane * per, NC), hi = min(lo + per, NC);
-    const bool cached = per <= kTabRegs;
-    Partial t[kTabRegs];
-#pragma unroll
-    for (int i = 0; i < kTabRegs; ++i) {
-        t[i] = Partial{kEInit, 0.f};
-        if (cached && lo + i < hi) t[i] = tab[lo + i];
-    }
     int Em = kEInit;
-    if (cached) {
-#pragma unroll
-        for (int i = 0; i < kTabRegs; ++i) Em = max(Em, t[i].E);
-    } else {
-        for (int c = lo; c < hi; ++c) Em = max(Em, tab[c].E);
-    }
+    for (int c = lo; c < hi; ++c) Em = max(Em, tab[c].E);
     const int Estar = wave_max_i32(Em);
     double lsum = 0.0;
-    if (cached) {
-#pragma unroll
-        for (int i = 0; i < kTabRegs; ++i) lsum += ldexp((double)t[i].s, t[i].E - Estar);
-    } else {
-        for (int c = lo; c < hi; ++c) lsum += ldexp((double)tab[c].s, tab[c].E - Estar);
-    }
+    for (int c = lo; c < hi; ++c) lsum += ldexp((double)tab[c].s, tab[c].E - Estar);
     const double incl = wave_incl_scan_f64(lsum, lane);
     const double total = __shfl(incl, 63, kWave);
     double excl = __shfl_up(incl, 1, kWave);
@@ -621,8 +534,8 @@ __device__ __forceinline__ void sample_wave(const RecArgs& a, int b, int n, int 
 
     int cfound = -1, clast = -1;
     double cbase = 0.0, cum = excl;
-    auto visit = [&](int c, const Partial& q) {
-        const double m = ldexp((double)q.s, q.E - Estar);
+    for (int c = lo; c < hi; ++c) {
+        const double m = ldexp((double)tab[c].s, tab[c].E - Estar);
         if (m > 0.0) clast = c;
         const double cum2 = cum + m;
         if (cfound < 0 && cum2 > target) {
@@ -630,13 +543,6 @@ __device__ __forceinline__ void sample_wave(const RecArgs& a, int b, int n, int 
             cbase = cum;
         }
         cum = cum2;
-    };
-    if (cached) {
-#pragma unroll
-        for (int i = 0; i < kTabRegs; ++i)
-            if (lo + i < hi) visit(lo + i, t[i]);
-    } else {
-        for (int c = lo; c < hi; ++c) visit(c, tab[c]);
     }
     const unsigned long long fmask = __ballot(cfound >= 0);
     int cstar;
@@ -652,185 +558,172 @@ __device__ __forceinline__ void sample_wave(const RecArgs& a, int b, int n, int 
         take_last = true;
     }
 
+    // re-read that chunk with each lane holding consecutive logits: one scan over the lanes
     const double dE = (double)Estar;
-    const int nsteps = (cstar < nch) ? kChunkSteps : 1;
-    // fetch the whole chunk first (one round trip), then walk it step by step
-    double yy[kChunkSteps][VEC];
-    long firsts[kChunkSteps];
-    int cnts[kChunkSteps];
+    float p[kChunkSteps][VEC];
+    long first[kChunkSteps];
+    int cnt[kChunkSteps];
+    chunk_lane_terms<DT, VEC>(g, sp, sm, nvec, tailc, nch, cstar, lane, a.c, a.bc, dE, p, first, cnt);
+    double ls = 0.0;
+    long lastpos = -1;
 #pragma unroll
     for (int j = 0; j < kChunkSteps; ++j) {
-        cnts[j] = 0;
-        firsts[j] = 0;
-        if (j < nsteps)
-            cnts[j] = chunk_lane_y<DT, VEC>(g, sp, sm, nvec, tailc, nch, cstar, j, lane, a.c, a.bc, yy[j], firsts[j]);
-    }
-    double run = base;
-    long tok = -1, lastpos = -1;
-    double ytok = 0.0, ylast = 0.0;
-#pragma unroll
-    for (int j = 0; j < kChunkSteps; ++j) {
-        if (j >= nsteps || tok >= 0) continue;
-        const int cnt = cnts[j];
-        const long first = firsts[j];
-        double p[VEC];
-        double ls = 0.0;
 #pragma unroll
         for (int i = 0; i < VEC; ++i) {
-            p[i] = (i < cnt) ? (double)__builtin_amdgcn_exp2f((float)(yy[j][i] - dE)) : 0.0;
-            ls += p[i];
-            if (i < cnt && p[i] > 0.0) {
-                lastpos = first + i;
-                ylast = yy[j][i];
-            }
+            ls += (double)p[j][i];
+            if (i < cnt[j] && p[j][i] > 0.f) lastpos = first[j] + i;
         }
-        const double inc = wave_incl_scan_f64(ls, lane);
-        double before = __shfl_up(inc, 1, kWave);
-        if (lane == 0) before = 0.0;
-        before += run;
-        long mytok = -1;
-        double myy = 0.0, cw = before;
-        if (!take_last) {
+    }
+    const double inc = wave_incl_scan_f64(ls, lane);
+    double cw = __shfl_up(inc, 1, kWave);
+    if (lane == 0) cw = 0.0;
+    cw += base;
+    long mytok = -1;
+    if (!take_last) {
+#pragma unroll
+        for (int j = 0; j < kChunkSteps; ++j) {
 #pragma unroll
             for (int i = 0; i < VEC; ++i) {
-                cw += p[i];
-                if (mytok < 0 && i < cnt && cw > target) {
-                    mytok = first + i;
-                    myy = yy[j][i];
-                }
+                cw += (double)p[j][i];
+                if (mytok < 0 && i < cnt[j] && cw > target) mytok = first[j] + i;
             }
         }
-        const unsigned long long hmask = __ballot(mytok >= 0);
-        if (hmask) {
-            const int L = first_lane(hmask);
-            tok = __shfl(mytok, L, kWave);
-            ytok = __shfl(myy, L, kWave);
-        }
-        run += __shfl(inc, 63, kWave);
     }
-    if (tok < 0) {
+    long tok;
+    const unsigned long long hmask = __ballot(mytok >= 0);
+    if (hmask) {
+        tok = __shfl(mytok, first_lane(hmask), kWave);
+    } else {
         // rounding between the chunk table and the re-read (or take_last): the last logit of
         // the chunk that still carries probability
         long best = lastpos;
 #pragma unroll
         for (int d = 1; d < kWave; d <<= 1) best = max(best, __shfl_xor(best, d, kWave));
-        const unsigned long long omask = __ballot(lastpos == best && best >= 0);
-        if (omask) {
-            tok = best;
-            ytok = __shfl(ylast, first_lane(omask), kWave);
-        } else {  // unreachable for finite logits; keep the index valid
-            tok = min((long)cstar * (kWave * kChunkSteps * VEC), (long)a.V - 1);
-            ytok = dE;
-        }
+        // no positive term at all is unreachable for finite logits; keep the index valid
+        tok = best >= 0 ? best : min((long)cstar * (kWave * kChunkSteps * VEC), (long)a.V - 1);
     }
+    // the chosen logit's exponent, read back in double (wave-uniform address)
+    const double ytok = rec_y(ld_elem<DT>(g, tok), ld_elem<DT>(sp, tok), ld_elem<DT>(sm, tok), a.c, a.bc);
     const double log2Z = dE + log2(total);
     if (lane == 0) {
-        a.log2Z[b] = log2Z;
         a.accepted_len[b] = n;
         a.next_token[b] = (int32_t)tok;
         if (a.next_token_logprob) a.next_token_logprob[b] = (float)(kLn2 * (ytok - log2Z));
     }
+    return log2Z;
 }
 
-// Work item = (sequence, chunk group).  Each wave takes a contiguous run of items, so it
-// repeats the (cheap) ratio test only when it moves on to another sequence; it then streams
-// its chunks of the three recovery rows and stores one mass per chunk.  Waves never wait for
-// or signal each other: the draw itself happens in the next kernel, after the launch boundary
-// has made every mass visible (a device-scope fence per item was measured to cost far more
-// than that launch, because it writes back and invalidates the whole L2 of the XCD).
+// One workgroup (16 waves) per sequence, everything after the row pass in one launch:
+//   2a  every (position, tensor) pair gets a wave: merge its slice partials, gather the draft
+//       token's logit, leave log P(y_t) in LDS            (two memory round trips in all)
+//   2b  wave 0: Eq. 7 on every position, first rejection by ballot
+//   3   all waves stream the three rows at the rejected (or bonus) position once, one (E, s)
+//       mass per 2048-logit chunk into LDS
+//   4   wave 0 draws the token; optionally all waves sweep the rows again to write log-probs
+// Only workgroup barriers separate the steps; nothing crosses workgroups.
 template <int DT, int VEC>
-__global__ __launch_bounds__(kRecThreads) void recover_kernel(const RecArgs a) {
-    const int lane = threadIdx.x & 63;
-    const long wave_global = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (kRecThreads / kWave) + (threadIdx.x >> 6)));
-    const long waves_total = (long)gridDim.x * (kRecThreads / kWave);
-    const long items = (long)a.B * a.NG;
-    const long per_wave = (items + waves_total - 1) / waves_total;
-    const long i0 = wave_global * per_wave;
-    const long i1 = min(items, i0 + per_wave);
-    const long nvec = a.V / VEC;
-    const int tailc = a.V - (int)(nvec * VEC);
-    const long nch = (nvec + kWave * kChunkSteps - 1) / (kWave * kChunkSteps);
+__global__ __launch_bounds__(kRecThreads) void accept_recover_kernel(const RecArgs a) {
+    extern __shared__ double smem_d[];
+    __shared__ int sh_n, sh_bad;
+    __shared__ double sh_log2Z;
 
-    int cur_b = -1, n = 0;
-    bool bad = false;
-    for (long i = i0; i < i1; ++i) {
-        const int b = (int)(i / a.NG);
-        const int j = (int)(i - (long)b * a.NG);
-        if (b != cur_b) {
-            // the wave holding group 0 of a sequence is the one that publishes its per-position outputs
-            ratio_test_wave<DT>(a, b, lane, j == 0, n, bad);
-            cur_b = b;
-            if (j == 0 && lane == 0) {
-                a.rec_row[b] = bad ? -1 : n;
-                if (bad) {
-                    a.accepted_len[b] = -1;
-                    a.next_token[b] = -1;
-                    if (a.next_token_logprob) a.next_token_logprob[b] = __int_as_float(0x7FC00000);
-                }
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int NW = kRecThreads / kWave;
+    const int kmax = a.kmax, V = a.V;
+    double* lp = smem_d;                                            // [kmax][2] log P_LLM, log P_SLM^-
+    Partial* tab = reinterpret_cast<Partial*>(smem_d + 2 * kmax);   // [NC] chunk masses
+
+    const int K = a.draft_len ? a.draft_len[b] : kmax;
+    const bool bad_len = (K < 0 || K > kmax);
+    if (tid == 0) sh_bad = bad_len ? 1 : 0;
+    __syncthreads();
+
+    // ---- 2a
+    if (!bad_len && K > 0) {
+        const long r0 = a.draft_len ? (long)a.row_off[b] : (long)b * kmax;
+        for (int q = wave; q < 2 * K; q += NW) {
+            const int t = q >> 1, x = q & 1;
+            const int y = a.draft[(long)b * kmax + t];  // wave-uniform
+            const bool ok = (y >= 0 && y < V);
+            const long off = (long)b * a.sb + (long)t * a.st;
+            const float h = ok ? ld_elem<DT>(row_ptr<DT>(x ? a.Sm : a.G, off), y) : 0.f;
+            const double L = combine_partials_wave(a.partial + ((r0 + t) * 2 + x) * a.NS, a.NS, lane);
+            if (lane == 0) {
+                lp[q] = kLn2 * ((double)h * a.c - L);
+                if (!ok) sh_bad = 1;
             }
-        }
-        if (bad) continue;
-        const long off = (long)b * a.sb + (long)n * a.st;
-        const void* g = row_ptr<DT>(a.G, off);
-        const void* sp = row_ptr<DT>(a.Sp, off);
-        const void* sm = row_ptr<DT>(a.Sm, off);
-        const int c0 = j * a.CG, c1 = min(a.NC, c0 + a.CG);
-        for (int c = c0; c < c1; ++c) {
-            const Partial p = chunk_mass<DT, VEC>(g, sp, sm, nvec, tailc, nch, c, lane, a.c, a.bc);
-            if (lane == 0) a.mass[(long)b * a.NC + c] = p;
         }
     }
-}
+    __syncthreads();
+    const bool bad = sh_bad != 0;
 
-// One wave per sequence: the inverse-CDF draw from the chunk masses of the recovery pass.
-template <int DT, int VEC>
-__global__ __launch_bounds__(kRecThreads) void sample_kernel(const RecArgs a) {
-    const int lane = threadIdx.x & 63;
-    const int b = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (kRecThreads / kWave) + (threadIdx.x >> 6)));
-    if (b >= a.B) return;
-    const int n = a.rec_row[b];
-    if (n < 0) return;  // flagged sequence, outputs already written
-    const long nvec = a.V / VEC;
-    const int tailc = a.V - (int)(nvec * VEC);
-    const long nch = (nvec + kWave * kChunkSteps - 1) / (kWave * kChunkSteps);
-    const long off = (long)b * a.sb + (long)n * a.st;
-    sample_wave<DT, VEC>(a, b, n, lane, row_ptr<DT>(a.G, off), row_ptr<DT>(a.Sp, off), row_ptr<DT>(a.Sm, off), nvec,
-                         tailc, nch);
-}
-
-// Optional second sweep: the whole log Softmax(h_rec / T) row of every sequence, same item
-// list as the recovery pass, using the normaliser and row index that pass left behind.
-template <int DT, int VEC>
-__global__ __launch_bounds__(kRecThreads) void logprob_rows_kernel(const RecArgs a) {
-    const int lane = threadIdx.x & 63;
-    const long wave_global = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (kRecThreads / kWave) + (threadIdx.x >> 6)));
-    const long waves_total = (long)gridDim.x * (kRecThreads / kWave);
-    const long items = (long)a.B * a.NG;
-    const long nvec = a.V / VEC;
-    const int tailc = a.V - (int)(nvec * VEC);
-    const long nch = (nvec + kWave * kChunkSteps - 1) / (kWave * kChunkSteps);
-    for (long i = wave_global; i < items; i += waves_total) {
-        const int b = (int)(i / a.NG);
-        const int j = (int)(i - (long)b * a.NG);
-        const int n = a.rec_row[b];
-        if (n < 0) continue;  // flagged sequence: row left unwritten
-        const double log2Z = a.log2Z[b];
-        const long off = (long)b * a.sb + (long)n * a.st;
-        const void* g = row_ptr<DT>(a.G, off);
-        const void* sp = row_ptr<DT>(a.Sp, off);
-        const void* sm = row_ptr<DT>(a.Sm, off);
-        float* out = a.recovery_logprobs + (long)b * a.V;
-        const int c0 = j * a.CG, c1 = min(a.NC, c0 + a.CG);
-        for (int c = c0; c < c1; ++c) {
-            const int nsteps = (c < nch) ? kChunkSteps : 1;
-            for (int s = 0; s < nsteps; ++s) {
-                double y[VEC];
-                long first;
-                const int cnt = chunk_lane_y<DT, VEC>(g, sp, sm, nvec, tailc, nch, c, s, lane, a.c, a.bc, y, first);
-#pragma unroll
-                for (int e = 0; e < VEC; ++e)
-                    if (e < cnt) out[first + e] = (float)(kLn2 * (y[e] - log2Z));
+    // ---- 2b
+    if (wave == 0 && !bad) {
+        int first_rej = K;
+        for (int t0 = 0; t0 < K; t0 += kWave) {
+            const int t = t0 + lane;
+            bool rej = false;
+            if (t < K) {
+                const double alpha = fmin(1.0, exp(lp[2 * t] - lp[2 * t + 1] - a.ln_lambda));  // Eq. 7
+                rej = !((double)a.uniforms[(long)b * (kmax + 1) + t] <= alpha);
             }
+            const unsigned long long rmask = __ballot(rej);
+            if (rmask && first_rej == K) first_rej = t0 + first_lane(rmask);
+        }
+        if (lane == 0) sh_n = first_rej;
+    }
+    if (a.draft_logprobs) {  // valid positions from LDS, padded slots 0, a flagged sequence NaN throughout
+        const float nanv = __int_as_float(0x7FC00000);
+        for (int i = tid; i < kmax * 2; i += kRecThreads)
+            a.draft_logprobs[(long)b * kmax * 2 + i] = bad ? nanv : (i < 2 * K ? (float)lp[i] : 0.f);
+    }
+    if (bad) {
+        if (tid == 0) {
+            a.accepted_len[b] = -1;
+            a.next_token[b] = -1;
+            if (a.next_token_logprob) a.next_token_logprob[b] = __int_as_float(0x7FC00000);
+        }
+        return;
+    }
+    __syncthreads();
+    const int n = sh_n;
+
+    // ---- 3
+    const long off = (long)b * a.sb + (long)n * a.st;
+    const void* g = row_ptr<DT>(a.G, off);
+    const void* sp = row_ptr<DT>(a.Sp, off);
+    const void* sm = row_ptr<DT>(a.Sm, off);
+    const long nvec = V / VEC;
+    const int tailc = V - (int)(nvec * VEC);
+    const long nch = (nvec + kWave * kChunkSteps - 1) / (kWave * kChunkSteps);
+    for (int c = wave; c < a.NC; c += NW) {
+        const Partial p = chunk_mass<DT, VEC>(g, sp, sm, nvec, tailc, nch, c, lane, a.c, a.bc);
+        if (lane == 0) tab[c] = p;
+    }
+    __syncthreads();
+
+    // ---- 4
+    if (wave == 0) {
+        const double log2Z = sample_wave<DT, VEC>(a, b, n, lane, tab, g, sp, sm, nvec, tailc, nch);
+        if (lane == 0) sh_log2Z = log2Z;
+    }
+    if (a.recovery_logprobs) {
+        __syncthreads();
+        const double log2Z = sh_log2Z;
+        float* out = a.recovery_logprobs + (long)b * V;
+        for (long v = tid; v < nvec; v += kRecThreads) {
+            float hg[VEC], hp[VEC], hm[VEC];
+            unpack(ld_raw<DT, VEC>(g, v), hg);
+            unpack(ld_raw<DT, VEC>(sp, v), hp);
+            unpack(ld_raw<DT, VEC>(sm, v), hm);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i)
+                out[v * VEC + i] = (float)(kLn2 * (rec_y(hg[i], hp[i], hm[i], a.c, a.bc) - log2Z));
+        }
+        if (tid < tailc) {
+            const long e = nvec * VEC + tid;
+            out[e] = (float)(kLn2 * (rec_y(ld_elem<DT>(g, e), ld_elem<DT>(sp, e), ld_elem<DT>(sm, e), a.c, a.bc) - log2Z));
         }
     }
 }
@@ -841,8 +734,7 @@ struct Plan {
     int vecfast;     // logits per 16-byte vector
     int NS;          // slices per row
     int slice_vecs;  // fast-width vectors per slice
-    int NCmax;       // upper bound of recovery chunks per row (element-wise path)
-    size_t off_log2z, off_recrow, off_mass, off_partial;
+    size_t off_partial;
     size_t bytes;
 };
 
@@ -870,7 +762,7 @@ Plan make_plan(const ss_params* p) {
     pl.vecfast = p->dtype == SS_BF16 ? 8 : 4;
     const long nvec = (p->vocab + pl.vecfast - 1) / pl.vecfast;
     const long rows2 = (long)p->batch * p->k_max * 2;
-    long ns_lo = (nvec + tune_slice_max() - 1) / tune_slice_max();
+    long ns_lo = (nvec + kMaxSliceVecs - 1) / kMaxSliceVecs;
     long ns_hi = (nvec + kMinSliceVecs - 1) / kMinSliceVecs;
     long want = rows2 > 0 ? (32768 + rows2 - 1) / rows2 : 1;
     long ns = want < ns_lo ? ns_lo : (want > ns_hi ? ns_hi : want);
@@ -882,13 +774,10 @@ Plan make_plan(const ss_params* p) {
     if (ns < 1) ns = 1;
     pl.NS = (int)ns;
     pl.slice_vecs = (int)sv;
-    pl.NCmax = chunks_per_row(p->vocab, 1);  // the element-wise path has the most chunks
     const size_t B = (size_t)p->batch;
-    size_t o = align_up((B + 1) * sizeof(int32_t), 256);           // row_off
-    pl.off_log2z = o;   o += align_up((B ? B : 1) * sizeof(double), 256);
-    pl.off_recrow = o;  o += align_up((B ? B : 1) * sizeof(int32_t), 256);
-    pl.off_mass = o;    o += align_up((B ? B : 1) * (size_t)pl.NCmax * sizeof(Partial), 256);
-    pl.off_partial = o; o += align_up((size_t)(rows2 > 0 ? rows2 : 1) * pl.NS * sizeof(Partial), 256);
+    size_t o = align_up((B + 1) * sizeof(int32_t), 256);  // row list of a ragged batch
+    pl.off_partial = o;
+    o += align_up((size_t)(rows2 > 0 ? rows2 : 1) * pl.NS * sizeof(Partial), 256);
     pl.bytes = o;
     return pl;
 }
@@ -922,33 +811,18 @@ hipError_t launch_all(LseArgs la, RecArgs ra, hipStream_t stream, hipEvent_t* ev
     if (items > 0) {  // row pass
         const long per_wg = kLseThreads / kWave;
         long wgs = (items + per_wg - 1) / per_wg;
-        const long cap = (long)cus * tune_wg_per_cu();
+        const long cap = (long)cus * kLseWgPerCu;
         if (wgs > cap) wgs = cap;
         const size_t lds = la.list_in_lds ? (size_t)(B + 1) * sizeof(int) : 0;
-        switch (tune_unroll()) {
-            case 8: hipLaunchKernelGGL((row_lse_kernel<DT, VEC, VECFAST, 8>), dim3((unsigned)wgs), dim3(kLseThreads), lds, stream, la); break;
-            default: hipLaunchKernelGGL((row_lse_kernel<DT, VEC, VECFAST, 4>), dim3((unsigned)wgs), dim3(kLseThreads), lds, stream, la); break;
-        }
+        hipLaunchKernelGGL((row_lse_kernel<DT, VEC, VECFAST, kLseUnroll>), dim3((unsigned)wgs), dim3(kLseThreads), lds,
+                           stream, la);
     }
     if (ev) hipEventRecord(ev[2], stream);
-    // recovery pass: enough chunk groups per sequence to give every resident wave a few items
+    // accept + recover: LDS holds the per-position log-probs and one mass per recovery chunk
     ra.NC = chunks_per_row(V, VEC);
-    const long waves = (long)cus * tune_rec_wg_per_cu() * (kRecThreads / kWave);
-    long ng = (4 * waves + B - 1) / B;
-    if (ng > ra.NC) ng = ra.NC;
-    if (ng < 1) ng = 1;
-    ra.CG = (int)((ra.NC + ng - 1) / ng);
-    ra.NG = (ra.NC + ra.CG - 1) / ra.CG;
-    const long ritems = (long)B * ra.NG;
-    long rwgs = (ritems + (kRecThreads / kWave) - 1) / (kRecThreads / kWave);
-    if (rwgs > (long)cus * tune_rec_wg_per_cu()) rwgs = (long)cus * tune_rec_wg_per_cu();
-    hipLaunchKernelGGL((recover_kernel<DT, VEC>), dim3((unsigned)rwgs), dim3(kRecThreads), 0, stream, ra);
-    const int swgs = (B + (kRecThreads / kWave) - 1) / (kRecThreads / kWave);
-    hipLaunchKernelGGL((sample_kernel<DT, VEC>), dim3((unsigned)swgs), dim3(kRecThreads), 0, stream, ra);
+    const size_t smem = (size_t)2 * kmax * sizeof(double) + (size_t)ra.NC * sizeof(Partial);
+    hipLaunchKernelGGL((accept_recover_kernel<DT, VEC>), dim3((unsigned)B), dim3(kRecThreads), smem, stream, ra);
     if (ev) hipEventRecord(ev[3], stream);
-    if (ra.recovery_logprobs)
-        hipLaunchKernelGGL((logprob_rows_kernel<DT, VEC>), dim3((unsigned)rwgs), dim3(kRecThreads), 0, stream, ra);
-    if (ev) hipEventRecord(ev[4], stream);
     return hipGetLastError();
 }
 
@@ -998,13 +872,10 @@ ss_status verify_block_impl(const void* G, const void* S_ctx, const void* S_noct
     RecArgs ra;
     ra.G = G; ra.Sp = S_ctx; ra.Sm = S_noctx; ra.draft = draft; ra.draft_len = draft_len; ra.uniforms = uniforms;
     ra.row_off = la.row_off; ra.partial = la.partial;
-    ra.mass = reinterpret_cast<Partial*>(ws + pl.off_mass);
-    ra.log2Z = reinterpret_cast<double*>(ws + pl.off_log2z);
-    ra.rec_row = reinterpret_cast<int32_t*>(ws + pl.off_recrow);
     ra.accepted_len = accepted_len; ra.next_token = next_token;
     ra.next_token_logprob = next_token_logprob; ra.recovery_logprobs = recovery_logprobs;
     ra.draft_logprobs = draft_logprobs; ra.sb = sb; ra.st = st; ra.B = params->batch; ra.kmax = params->k_max;
-    ra.V = params->vocab; ra.NS = pl.NS; ra.NC = 0; ra.NG = 1; ra.CG = 1; ra.c = c;
+    ra.V = params->vocab; ra.NS = pl.NS; ra.NC = 0; ra.c = c;
     ra.bc = (double)params->beta * c; ra.ln_lambda = std::log((double)params->lambda);
 
     hipStream_t s = static_cast<hipStream_t>(stream);
