@@ -52,6 +52,7 @@ def main() -> int:
     ap.add_argument("--sets", type=int, default=2, help="rotating input sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--lam", type=float, default=None, help="override the verification threshold")
+    ap.add_argument("--dense", action="store_true", help="ignore the length array of a ragged workload (K_b = k_max)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device copies (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -76,6 +77,9 @@ def main() -> int:
     esz = 2 if w.dtype == "bf16" else 4
 
     sets = [W.generate(w, dev, seed_shift=i) for i in range(max(1, args.sets))]
+    if args.dense:
+        for s_ in sets:
+            s_["draft_len"] = None
     B, kmax, V = w.batch, w.k_max, w.vocab
     params = binding.make_params(B, kmax, V, W.torch_dtype(w.dtype), lam=w.lam, beta=w.beta,
                                  temperature=w.temperature)

@@ -103,14 +103,38 @@ __device__ __forceinline__ float wave_sum_f32(float x) {
     return (a + b) + (c + d);
 }
 
-// Inclusive prefix sum over the 64 lanes (rare, per-sequence scalar work: plain shuffles).
-__device__ __forceinline__ double wave_incl_scan_f64(double x, int lane) {
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const double y = __shfl_up(x, d, kWave);
-        if (lane >= d) x += y;
-    }
+// One DPP move of a double (both halves); lanes the pattern leaves without a source, or that
+// row_mask disables, receive 0.0.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_f64_or_zero(double x) {
+    const long long b = __double_as_longlong(x);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(b & 0xFFFFFFFFll), CTRL, ROW_MASK, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, ROW_MASK, 0xF, false);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+constexpr int kDppRowShr1 = 0x111, kDppRowShr2 = 0x112, kDppRowShr4 = 0x114, kDppRowShr8 = 0x118;
+constexpr int kDppRowBcast15 = 0x142;  // lane 15 of each row -> every lane of the next row
+constexpr int kDppRowBcast31 = 0x143;  // lane 31 -> every lane of rows 2 and 3
+constexpr int kDppWaveShr1 = 0x138;    // lane i-1 -> lane i across the whole wave
+
+// Inclusive prefix sum over the 64 lanes: Hillis-Steele inside each row of 16, then the row totals.
+__device__ __forceinline__ double wave_incl_scan_f64(double x) {
+    x += dpp_f64_or_zero<kDppRowShr1, 0xF>(x);
+    x += dpp_f64_or_zero<kDppRowShr2, 0xF>(x);
+    x += dpp_f64_or_zero<kDppRowShr4, 0xF>(x);
+    x += dpp_f64_or_zero<kDppRowShr8, 0xF>(x);
+    x += dpp_f64_or_zero<kDppRowBcast15, 0xA>(x);  // rows 1 and 3 take in the row before them
+    x += dpp_f64_or_zero<kDppRowBcast31, 0xC>(x);  // rows 2 and 3 take in the first half
     return x;
+}
+
+// Exclusive companion of an inclusive scan result (lane 0 gets 0) and the wave total.
+__device__ __forceinline__ double wave_shift_up_f64(double incl) { return dpp_f64_or_zero<kDppWaveShr1, 0xF>(incl); }
+__device__ __forceinline__ double wave_last_f64(double incl) {
+    const long long b = __double_as_longlong(incl);
+    const int lo = __builtin_amdgcn_readlane((int)(b & 0xFFFFFFFFll), 63);
+    const int hi = __builtin_amdgcn_readlane((int)(b >> 32), 63);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
 }
 
 __device__ __forceinline__ int first_lane(unsigned long long mask) { return __ffsll((long long)mask) - 1; }
@@ -187,10 +211,12 @@ __device__ __forceinline__ int exp_ref(float scaled_max) {
     return (int)ceilf(fminf(fmaxf(scaled_max, -kEClamp), kEClamp));
 }
 
-// fp32 path of the row pass: term = 2^(h*c - E) with c = c_hi + c_lo carried as two floats,
-// so the rounding of c does not scale with |h| (it would cost |h/T| * 2^-24 in the log-sum).
+// fp32 path of the row pass: term = 2^(h*c_hi - E), c_hi = fl32(c).  The rounding of c would cost
+// |h/T| * 2^-24 in the log-sum; it is repaid when the partials are merged: with z = h*c_hi - E
+// the missing factor is 2^((z + E)*rho), rho = (c - c_hi)/c_hi ~ 2^-25, and the terms that carry
+// the sum have |z| of a few units, so adding E*rho to the row's log2-sum leaves ~|z|*rho < 1e-6.
 template <int N>
-__device__ __forceinline__ void acc_add_f32(Acc& a, const float (&h)[N], float c_hi, float c_lo) {
+__device__ __forceinline__ void acc_add_f32(Acc& a, const float (&h)[N], float c_hi) {
     float m = h[0];
 #pragma unroll
     for (int i = 1; i < N; ++i) m = fmaxf(m, h[i]);
@@ -201,8 +227,8 @@ __device__ __forceinline__ void acc_add_f32(Acc& a, const float (&h)[N], float c
     float t0 = 0.f, t1 = 0.f;
 #pragma unroll
     for (int i = 0; i < N; i += 2) {
-        t0 += __builtin_amdgcn_exp2f(fmaf(h[i], c_lo, fmaf(h[i], c_hi, nE)));
-        if (i + 1 < N) t1 += __builtin_amdgcn_exp2f(fmaf(h[i + 1], c_lo, fmaf(h[i + 1], c_hi, nE)));
+        t0 += __builtin_amdgcn_exp2f(fmaf(h[i], c_hi, nE));
+        if (i + 1 < N) t1 += __builtin_amdgcn_exp2f(fmaf(h[i + 1], c_hi, nE));
     }
     a.s += t0 + t1;
 }
@@ -308,7 +334,7 @@ struct LseArgs {
     int B, kmax, V, NS;
     int slice_vecs;            // vectors (of the fast path's width) per slice
     int list_in_lds;           // ragged: build the row list in LDS (else row_off was filled by prep_rows)
-    float c_hi, c_lo;
+    float c_hi;                // fl32(log2(e)/T)
 };
 
 // Work item = (row, tensor, slice), flattened so that consecutive items are consecutive slices
@@ -375,16 +401,16 @@ __global__ __launch_bounds__(kLseThreads) void row_lse_kernel(const LseArgs a) {
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) h[j * VEC + i] = hj[i];
             }
-            acc_add_f32<kUnroll * VEC>(acc, h, a.c_hi, a.c_lo);
+            acc_add_f32<kUnroll * VEC>(acc, h, a.c_hi);
         }
         for (; v < v1; v += kWave) {
             float hj[VEC];
             unpack(ld_raw<DT, VEC>(row, v), hj);
-            acc_add_f32<VEC>(acc, hj, a.c_hi, a.c_lo);
+            acc_add_f32<VEC>(acc, hj, a.c_hi);
         }
         if (k == a.NS - 1 && lane < tailc) {  // logits past the last full vector
             float hj[1] = {ld_elem<DT>(row, nvec * VEC + lane)};
-            acc_add_f32<1>(acc, hj, a.c_hi, a.c_lo);
+            acc_add_f32<1>(acc, hj, a.c_hi);
         }
         const Partial p = wave_combine(acc);
         if (lane == 0) a.partial[item] = p;
@@ -413,11 +439,12 @@ struct RecArgs {
     double c;        // log2(e) / T
     double bc;       // beta * log2(e) / T
     double ln_lambda;
+    double rho;      // (c - fl32(c)) / fl32(c): first-order repair of the row pass's rounded scale
 };
 
 // log2 of sum_v 2^(h_v * c) for one row from its slice partials, by one wave: lane k holds
 // slice k (one coalesced load for up to 64 slices), the merge is two DPP reductions.
-__device__ __forceinline__ double combine_partials_wave(const Partial* p, int NS, int lane) {
+__device__ __forceinline__ double combine_partials_wave(const Partial* p, int NS, int lane, double rho) {
     Acc q{kEInit, 0.f};
     if (lane < NS) {
         const Partial v = p[lane];
@@ -425,7 +452,7 @@ __device__ __forceinline__ double combine_partials_wave(const Partial* p, int NS
         q.s = v.s;
     }
     const Partial m = wave_combine(q);
-    return (double)m.E + log2((double)m.s);
+    return (double)m.E * (1.0 + rho) + log2((double)m.s);  // E*rho: see acc_add_f32
 }
 
 // Probability terms 2^(y - E*) of the logits one lane owns in recovery chunk c, laid out so that
@@ -526,10 +553,9 @@ __device__ __forceinline__ double sample_wave(const RecArgs& a, int b, int n, in
     const int Estar = wave_max_i32(Em);
     double lsum = 0.0;
     for (int c = lo; c < hi; ++c) lsum += ldexp((double)tab[c].s, tab[c].E - Estar);
-    const double incl = wave_incl_scan_f64(lsum, lane);
-    const double total = __shfl(incl, 63, kWave);
-    double excl = __shfl_up(incl, 1, kWave);
-    if (lane == 0) excl = 0.0;
+    const double incl = wave_incl_scan_f64(lsum);
+    const double total = wave_last_f64(incl);
+    const double excl = wave_shift_up_f64(incl);
     const double target = us * total;
 
     int cfound = -1, clast = -1;
@@ -574,36 +600,41 @@ __device__ __forceinline__ double sample_wave(const RecArgs& a, int b, int n, in
             if (i < cnt[j] && p[j][i] > 0.f) lastpos = first[j] + i;
         }
     }
-    const double inc = wave_incl_scan_f64(ls, lane);
-    double cw = __shfl_up(inc, 1, kWave);
-    if (lane == 0) cw = 0.0;
-    cw += base;
+    double cw = wave_shift_up_f64(wave_incl_scan_f64(ls)) + base;
     long mytok = -1;
-    if (!take_last) {
+    float ptok = 0.f, plast = 0.f;
 #pragma unroll
-        for (int j = 0; j < kChunkSteps; ++j) {
+    for (int j = 0; j < kChunkSteps; ++j) {
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) {
-                cw += (double)p[j][i];
-                if (mytok < 0 && i < cnt[j] && cw > target) mytok = first[j] + i;
+        for (int i = 0; i < VEC; ++i) {
+            cw += (double)p[j][i];
+            if (i < cnt[j] && p[j][i] > 0.f) plast = p[j][i];
+            if (!take_last && mytok < 0 && i < cnt[j] && cw > target) {
+                mytok = first[j] + i;
+                ptok = p[j][i];
             }
         }
     }
     long tok;
     const unsigned long long hmask = __ballot(mytok >= 0);
     if (hmask) {
-        tok = __shfl(mytok, first_lane(hmask), kWave);
+        const int L = first_lane(hmask);
+        tok = __shfl(mytok, L, kWave);
+        ptok = __shfl(ptok, L, kWave);
     } else {
         // rounding between the chunk table and the re-read (or take_last): the last logit of
         // the chunk that still carries probability
         long best = lastpos;
 #pragma unroll
         for (int d = 1; d < kWave; d <<= 1) best = max(best, __shfl_xor(best, d, kWave));
+        const unsigned long long omask = __ballot(lastpos == best && best >= 0);
         // no positive term at all is unreachable for finite logits; keep the index valid
-        tok = best >= 0 ? best : min((long)cstar * (kWave * kChunkSteps * VEC), (long)a.V - 1);
+        tok = omask ? best : min((long)cstar * (kWave * kChunkSteps * VEC), (long)a.V - 1);
+        ptok = omask ? __shfl(plast, first_lane(omask), kWave) : 1.f;
     }
-    // the chosen logit's exponent, read back in double (wave-uniform address)
-    const double ytok = rec_y(ld_elem<DT>(g, tok), ld_elem<DT>(sp, tok), ld_elem<DT>(sm, tok), a.c, a.bc);
+    // the chosen logit's exponent back from its term: 2^(y - E*) is a normal fp32 number with one
+    // ulp of error, so log2 of it is good to ~2e-7 whatever the magnitude of y
+    const double ytok = dE + log2((double)ptok);
     const double log2Z = dE + log2(total);
     if (lane == 0) {
         a.accepted_len[b] = n;
@@ -648,7 +679,7 @@ __global__ __launch_bounds__(kRecThreads) void accept_recover_kernel(const RecAr
             const bool ok = (y >= 0 && y < V);
             const long off = (long)b * a.sb + (long)t * a.st;
             const float h = ok ? ld_elem<DT>(row_ptr<DT>(x ? a.Sm : a.G, off), y) : 0.f;
-            const double L = combine_partials_wave(a.partial + ((r0 + t) * 2 + x) * a.NS, a.NS, lane);
+            const double L = combine_partials_wave(a.partial + ((r0 + t) * 2 + x) * a.NS, a.NS, lane, a.rho);
             if (lane == 0) {
                 lp[q] = kLn2 * ((double)h * a.c - L);
                 if (!ok) sh_bad = 1;
@@ -857,17 +888,15 @@ ss_status verify_block_impl(const void* G, const void* S_ctx, const void* S_noct
 
     char* ws = static_cast<char*>(workspace);
 
-    // c = log2(e)/T as an unevaluated sum of two floats for the fp32 row pass
     const double T = (double)params->temperature;
     const double c = kLog2e / T;
-    const float c_hi = (float)c;
-    const float c_lo = (float)(c - (double)c_hi);
+    const float c_hi = (float)c;  // the row pass scales by this; the merge repairs the difference
 
     LseArgs la;
     la.G = G; la.Sm = S_noctx; la.draft_len = draft_len; la.row_off = reinterpret_cast<int32_t*>(ws);
     la.partial = reinterpret_cast<Partial*>(ws + pl.off_partial);
     la.sb = sb; la.st = st; la.B = params->batch; la.kmax = params->k_max; la.V = params->vocab;
-    la.NS = pl.NS; la.slice_vecs = pl.slice_vecs; la.list_in_lds = 0; la.c_hi = c_hi; la.c_lo = c_lo;
+    la.NS = pl.NS; la.slice_vecs = pl.slice_vecs; la.list_in_lds = 0; la.c_hi = c_hi;
 
     RecArgs ra;
     ra.G = G; ra.Sp = S_ctx; ra.Sm = S_noctx; ra.draft = draft; ra.draft_len = draft_len; ra.uniforms = uniforms;
@@ -877,6 +906,7 @@ ss_status verify_block_impl(const void* G, const void* S_ctx, const void* S_noct
     ra.draft_logprobs = draft_logprobs; ra.sb = sb; ra.st = st; ra.B = params->batch; ra.kmax = params->k_max;
     ra.V = params->vocab; ra.NS = pl.NS; ra.NC = 0; ra.c = c;
     ra.bc = (double)params->beta * c; ra.ln_lambda = std::log((double)params->lambda);
+    ra.rho = (c - (double)c_hi) / (double)c_hi;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t err;
