@@ -69,8 +69,17 @@ typedef struct {
     float lambda;        /* verification threshold of Eq. 7; finite, > 0. Paper default 0.5    */
     float beta;          /* steering-recovery strength of Eq. 8; finite. Paper default 1.0     */
     float temperature;   /* T; finite, > 0. 1.0 reproduces the paper                           */
-    uint32_t flags;      /* must be 0                                                          */
+    uint32_t flags;      /* 0, or SS_FLAG_GREEDY; any other bit is an error                    */
 } ss_params;
+
+/*
+ * Greedy decoding, the setting of the paper's experiments ("we use greedy decoding"): the
+ * ratio test of Eq. 7 is unchanged, but the correction / bonus token is the mode of the recovery
+ * distribution, argmax_v of Eq. 8's h_rec(v) (lowest index on ties), instead of a draw;
+ * uniforms[b][k_max] is not read.  h_rec is evaluated for this purpose as
+ * h_LLM + beta * (h_SLM^+ - h_SLM^-) in double precision with no fused multiply-add.
+ */
+#define SS_FLAG_GREEDY 1u
 
 /*
  * Bytes of device scratch specsteer_verify_block needs for these params
@@ -82,7 +91,8 @@ size_t specsteer_workspace_bytes(const ss_params *params);
 /*
  * The block (Algorithm 1 phases 2-3, Eq. 7, Eq. 8; see the top of this file).
  *
- *   G, S_ctx, S_noctx  device, [B, k_max+1, V] logits of params->dtype.  The fast
+ *   G, S_ctx, S_noctx  device, [B, k_max+1, V] logits of params->dtype.  With beta == 0 the
+ *                      recovery distribution is Softmax(G/T) and S_ctx is not read.  The fast
  *                      path needs all three base pointers 16-byte aligned and both
  *                      strides multiples of 16 bytes; anything else (any V, any
  *                      element-aligned pointer) takes a slower element-wise path.

@@ -34,13 +34,14 @@ class _Params(ctypes.Structure):
         ("beta", ctypes.c_float),
         ("temperature", ctypes.c_float),
         ("num_threads", ctypes.c_int32),
+        ("greedy", ctypes.c_int32),
     ]
 
 
 def build(force: bool = False) -> str:
     """Compile the C oracle into a shared library next to its source."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"]
+        cmd = ["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -90,7 +91,7 @@ def _int32(x):
 
 
 def verify_block(G, S_ctx, S_noctx, draft, uniforms, *, lam=0.5, beta=1.0, temperature=1.0,
-                 draft_len=None, want_recovery_logprobs=True, num_threads=1):
+                 draft_len=None, want_recovery_logprobs=True, num_threads=1, greedy=False):
     """Run the oracle on host arrays shaped [B, k_max+1, V] (logits), [B, k_max]
     (draft), [B, k_max+1] (uniforms).  Returns a dict of numpy arrays."""
     g, dt = _logits_array(G)
@@ -107,7 +108,8 @@ def verify_block(G, S_ctx, S_noctx, draft, uniforms, *, lam=0.5, beta=1.0, tempe
     u = np.ascontiguousarray(uniforms, dtype=np.float32).reshape(B, k1)
     dl = None if draft_len is None else _int32(draft_len).reshape(B)
 
-    p = _Params(B, kmax, V, dt, 0, 0, float(lam), float(beta), float(temperature), int(num_threads))
+    p = _Params(B, kmax, V, dt, 0, 0, float(lam), float(beta), float(temperature), int(num_threads),
+                1 if greedy else 0)
     acc = np.empty(B, np.int32)
     tok = np.empty(B, np.int32)
     tok_lp = np.empty(B, np.float64)

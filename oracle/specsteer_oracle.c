@@ -26,7 +26,9 @@
  *   - the sampled token is the inverse CDF in vocabulary-index order:
  *     the first j whose inclusive cumulative probability exceeds the uniform.
  *
- * Build: gcc -O2 -fopenmp -shared -fPIC -o libspecsteer_oracle.so specsteer_oracle.c -lm
+ * Build: gcc -O2 -ffp-contract=off -fopenmp -shared -fPIC -o libspecsteer_oracle.so specsteer_oracle.c -lm
+ * (no fused multiply-add: Eq. 8 is one multiply and one add, each rounded, so that an argmax over
+ * it is reproducible bit for bit)
  * The OpenMP loop runs over the independent sequences only and changes no
  * arithmetic; it exists so the benchmark can time the oracle on all host cores.
  */
@@ -51,6 +53,8 @@ typedef struct {
     float beta;          /* steering-recovery strength (Eq. 8) */
     float temperature;   /* T > 0 */
     int32_t num_threads; /* OpenMP threads over sequences; <=1 => serial */
+    int32_t greedy;      /* 0: draw the token by inverse CDF; 1: take argmax h_rec (lowest index on ties),
+                            the deterministic decoding the paper's experiments use in place of "Sample" */
 } sso_params;
 
 /* Exact widening of one stored logit to double. */
@@ -128,11 +132,18 @@ static void verify_one(const void *G, const void *Sp, const void *Sm, const int3
 
     /* Phase 3 (or bonus): Eq. 8 at row n, then Softmax and one inverse-CDF draw. */
     const int64_t off = seq_off + (int64_t)n * st;
+    int amax = 0;
+    double hmax = -INFINITY;
     for (int v = 0; v < V; ++v) {
         const double hl = widen(G, dt, off + v);
         const double hp = widen(Sp, dt, off + v);
         const double hm = widen(Sm, dt, off + v);
-        g[v] = (hl + beta * (hp - hm)) / T;
+        const double hrec = hl + beta * (hp - hm); /* Eq. 8 */
+        if (hrec > hmax) { /* strict: the lowest index wins a tie */
+            hmax = hrec;
+            amax = v;
+        }
+        g[v] = hrec / T;
     }
     const double lse = log_sum_exp(g, V);
     for (int v = 0; v < V; ++v) g[v] -= lse; /* g is now log Softmax(h_rec / T) */
@@ -150,6 +161,10 @@ static void verify_one(const void *G, const void *Sp, const void *Sm, const int3
         if (d < margin) margin = d;
     }
     if (tok < 0) tok = last_pos; /* only reachable through rounding when us is within an ulp of 1 */
+    if (p->greedy) {
+        tok = amax;
+        margin = INFINITY; /* no uniform is involved: nothing excuses a mismatch */
+    }
 
     *accepted_len = n;
     *next_token = tok;

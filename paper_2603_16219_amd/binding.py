@@ -15,6 +15,7 @@ import torch  # imported before the library so both share one HIP runtime
 from . import build as _build
 
 SS_F32, SS_BF16 = 0, 1
+SS_FLAG_GREEDY = 1
 _STATUS_OK = 0
 
 
@@ -119,7 +120,8 @@ def verify_block_raw(G, S_ctx, S_noctx, draft, draft_len, uniforms, params: SSPa
 def verify_block(G: torch.Tensor, S_ctx: torch.Tensor, S_noctx: torch.Tensor, draft: torch.Tensor,
                  uniforms: torch.Tensor, *, lam: float = 0.5, beta: float = 1.0, temperature: float = 1.0,
                  draft_len: Optional[torch.Tensor] = None, want_recovery_logprobs: bool = False,
-                 want_draft_logprobs: bool = False, workspace: Optional[torch.Tensor] = None) -> dict:
+                 want_draft_logprobs: bool = False, workspace: Optional[torch.Tensor] = None,
+                 greedy: bool = False) -> dict:
     """specsteer_verify_block on device tensors G/S_ctx/S_noctx [B, k_max+1, V] (vocab stride 1),
     draft [B, k_max] int32, uniforms [B, k_max+1] float32.  Allocates the outputs (and a workspace
     unless one is given) with torch and returns them in a dict; runs on torch's current stream."""
@@ -139,7 +141,8 @@ def verify_block(G: torch.Tensor, S_ctx: torch.Tensor, S_noctx: torch.Tensor, dr
     if draft_len is not None:
         draft_len = draft_len.to(device=dev, dtype=torch.int32).contiguous()
     params = make_params(B, k_max, V, G.dtype, lam=lam, beta=beta, temperature=temperature,
-                         stride_b=G.stride(0) if B > 1 else 0, stride_t=G.stride(1) if k1 > 1 else 0)
+                         stride_b=G.stride(0) if B > 1 else 0, stride_t=G.stride(1) if k1 > 1 else 0,
+                         flags=SS_FLAG_GREEDY if greedy else 0)
     need = workspace_bytes(params)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
@@ -154,3 +157,25 @@ def verify_block(G: torch.Tensor, S_ctx: torch.Tensor, S_noctx: torch.Tensor, dr
                      out["accepted_len"], out["next_token"], out["next_token_logprob"],
                      out["recovery_logprobs"], out["draft_logprobs"], workspace)
     return out
+
+
+def steer_rows(G: torch.Tensor, S_ctx: torch.Tensor, S_noctx: torch.Tensor, uniforms: torch.Tensor, *,
+               beta: float = 1.0, temperature: float = 1.0, greedy: bool = False,
+               want_logprobs: bool = False) -> dict:
+    """Always-on steering: the recovery distribution of Eq. 8 applied to EVERY row ([N, V] logits,
+    one uniform per row) -- the per-token fusion the paper compares against.  This is the same entry
+    point with no drafted positions (k_max = 0): each row is a one-row sequence whose bonus token is
+    drawn from softmax((G + beta (S_ctx - S_noctx)) / T)."""
+    n, v = G.shape
+    out = verify_block(G.view(n, 1, v), S_ctx.view(n, 1, v), S_noctx.view(n, 1, v),
+                       torch.empty(n, 0, dtype=torch.int32, device=G.device), uniforms.reshape(n, 1),
+                       beta=beta, temperature=temperature, want_recovery_logprobs=want_logprobs, greedy=greedy)
+    return {"token": out["next_token"], "token_logprob": out["next_token_logprob"],
+            "logprobs": out["recovery_logprobs"]}
+
+
+def sample_rows(logits: torch.Tensor, uniforms: torch.Tensor, *, temperature: float = 1.0,
+                greedy: bool = False) -> dict:
+    """Plain softmax sampling of [N, V] rows by inverse CDF (Eq. 5, the drafting step, when the rows are
+    the specialist's): the block with k_max = 0 and beta = 0, which reads each row once."""
+    return steer_rows(logits, logits, logits, uniforms, beta=0.0, temperature=temperature, greedy=greedy)

@@ -38,10 +38,21 @@ namespace {
 
 constexpr int kWave = 64;
 constexpr int kLseThreads = 256;            // 4 independent waves per workgroup
-constexpr int kLseUnroll = 4;               // 16-byte loads in flight per lane
-constexpr int kLseWgPerCu = 4;              // persistent workgroups per CU (16 waves/CU measured fastest)
+// Launch-shape constants of the row pass; the defaults are the measured optimum on MI355X for
+// the B=256, V=128256 bf16 workload and can be overridden at build time for other sweeps.
+#ifndef SS_LSE_UNROLL
+#define SS_LSE_UNROLL 4
+#endif
+#ifndef SS_LSE_WG_PER_CU
+#define SS_LSE_WG_PER_CU 4
+#endif
+#ifndef SS_LSE_MAX_SLICE_VECS
+#define SS_LSE_MAX_SLICE_VECS 4096
+#endif
+constexpr int kLseUnroll = SS_LSE_UNROLL;   // 16-byte loads in flight per lane
+constexpr int kLseWgPerCu = SS_LSE_WG_PER_CU;  // persistent workgroups per CU
 constexpr int kMinSliceVecs = kWave * kLseUnroll;  // smallest slice: one unrolled group
-constexpr int kMaxSliceVecs = 4096;         // 64 KiB of logits per slice
+constexpr int kMaxSliceVecs = SS_LSE_MAX_SLICE_VECS;  // 64 KiB of logits per slice
 constexpr int kMaxSlices = 64;
 constexpr int kMaxLdsBatch = 8192;          // ragged batches up to this size keep their row list in LDS
 constexpr int kChunkSteps = 4;              // recovery chunk = 4 wave-steps (2048 bf16 logits)
@@ -245,9 +256,29 @@ __device__ __forceinline__ double rec_y(float g, float sp, float sm, double c, d
 // exponential.  sp - sm is taken in fp32: exact for bf16 inputs whose exponents differ by
 // less than 16 (otherwise the smaller one is below 2^-16 of the larger and the difference
 // rounds by at most 2^-25 of it); fp32 inputs widen first.
-template <int DT, int N>
+// Greedy decoding needs argmax of Eq. 8 itself: h_LLM + beta*(h_SLM^+ - h_SLM^-) as one exact
+// difference, one rounded product and one rounded sum in double -- the same three operations
+// the definition spells out, so the winner is reproducible bit for bit.  Strict '>' keeps the
+// lowest index, because a lane meets its logits in increasing vocabulary order.
+struct Best {
+    double v;
+    long idx;
+};
+
+template <int DT, int N, bool GREEDY>
 __device__ __forceinline__ void acc_add_rec(Acc& a, const float (&hg)[N], const float (&hp)[N], const float (&hm)[N],
-                                            double c, double bc, float cf, float bcf) {
+                                            double c, double bc, float cf, float bcf, double beta, long first,
+                                            Best& best) {
+    if (GREEDY) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const double hr = __dadd_rn((double)hg[i], __dmul_rn(beta, (double)hp[i] - (double)hm[i]));
+            if (hr > best.v) {
+                best.v = hr;
+                best.idx = first + i;
+            }
+        }
+    }
     float d[N];
     float m = -3.0e38f;
 #pragma unroll
@@ -421,8 +452,9 @@ __global__ __launch_bounds__(kLseThreads) void row_lse_kernel(const LseArgs a) {
 
 struct RecArgs {
     const void* G;
-    const void* Sp;
-    const void* Sm;
+    const void* Sm;          // S_noctx, for the ratio test
+    const void* recSp;       // S_ctx and S_noctx as the recovery sweep reads them: both alias G when
+    const void* recSm;       //   beta == 0, so that the steering term is an exact zero and costs no HBM traffic
     const int32_t* draft;
     const int32_t* draft_len;
     const float* uniforms;
@@ -438,8 +470,10 @@ struct RecArgs {
     int NC;          // chunks per row (full chunks + one pseudo-chunk for the logits past the last vector)
     double c;        // log2(e) / T
     double bc;       // beta * log2(e) / T
+    double beta;     // beta itself, for the greedy argmax of Eq. 8
     double ln_lambda;
     double rho;      // (c - fl32(c)) / fl32(c): first-order repair of the row pass's rounded scale
+    int greedy;      // SS_FLAG_GREEDY
 };
 
 // log2 of sum_v 2^(h_v * c) for one row from its slice partials, by one wave: lane k holds
@@ -500,9 +534,10 @@ __device__ __forceinline__ void chunk_lane_terms(const void* g, const void* sp, 
 }
 
 // (E, s) mass of recovery chunk c, by one wave: sum over the chunk of 2^(y - E).
-template <int DT, int VEC>
+template <int DT, int VEC, bool GREEDY>
 __device__ __forceinline__ Partial chunk_mass(const void* g, const void* sp, const void* sm, long nvec, int tailc,
-                                              long nch, long c, int lane, double cc, double bc) {
+                                              long nch, long c, int lane, double cc, double bc, double beta,
+                                              Best& best) {
     const float cf = (float)cc, bcf = (float)bc;
     Acc acc{kEInit, 0.f};
     if (c < nch) {
@@ -525,13 +560,13 @@ __device__ __forceinline__ Partial chunk_mass(const void* g, const void* sp, con
                 unpack(rg[j], hg);
                 unpack(rp[j], hp);
                 unpack(rm[j], hm);
-                acc_add_rec<DT, VEC>(acc, hg, hp, hm, cc, bc, cf, bcf);
+                acc_add_rec<DT, VEC, GREEDY>(acc, hg, hp, hm, cc, bc, cf, bcf, beta, v * VEC, best);
             }
         }
     } else if (lane < tailc) {
         const long e = nvec * VEC + lane;
         const float hg[1] = {ld_elem<DT>(g, e)}, hp[1] = {ld_elem<DT>(sp, e)}, hm[1] = {ld_elem<DT>(sm, e)};
-        acc_add_rec<DT, 1>(acc, hg, hp, hm, cc, bc, cf, bcf);
+        acc_add_rec<DT, 1, GREEDY>(acc, hg, hp, hm, cc, bc, cf, bcf, beta, e, best);
     }
     return wave_combine(acc);
 }
@@ -539,10 +574,10 @@ __device__ __forceinline__ Partial chunk_mass(const void* g, const void* sp, con
 // Inverse-CDF draw for one sequence by one wave, from the chunk masses `tab` (LDS) of its
 // recovery row: a double-precision scan over the masses finds the chunk holding u*Z, and only
 // that chunk is read again to pick the token.  Returns log2 Z; writes the per-sequence outputs.
-template <int DT, int VEC>
+template <int DT, int VEC, bool GREEDY>
 __device__ __forceinline__ double sample_wave(const RecArgs& a, int b, int n, int lane, const Partial* tab,
                                               const void* g, const void* sp, const void* sm, long nvec, int tailc,
-                                              long nch) {
+                                              long nch, Best greedy_pick) {
     const int NC = a.NC;
     const double us = (double)a.uniforms[(long)b * (a.kmax + 1) + a.kmax];
     // each lane owns a contiguous run of `per` chunks
@@ -555,6 +590,16 @@ __device__ __forceinline__ double sample_wave(const RecArgs& a, int b, int n, in
     for (int c = lo; c < hi; ++c) lsum += ldexp((double)tab[c].s, tab[c].E - Estar);
     const double incl = wave_incl_scan_f64(lsum);
     const double total = wave_last_f64(incl);
+    if (GREEDY) {  // the token is already known; only the normaliser is needed
+        const double log2Z = (double)Estar + log2(total);
+        const long tok = min(max(greedy_pick.idx, 0l), (long)a.V - 1);
+        if (lane == 0) {
+            a.accepted_len[b] = n;
+            a.next_token[b] = (int32_t)tok;
+            if (a.next_token_logprob) a.next_token_logprob[b] = (float)(kLn2 * (greedy_pick.v * a.c - log2Z));
+        }
+        return log2Z;
+    }
     const double excl = wave_shift_up_f64(incl);
     const double target = us * total;
 
@@ -652,11 +697,13 @@ __device__ __forceinline__ double sample_wave(const RecArgs& a, int b, int n, in
 //       mass per 2048-logit chunk into LDS
 //   4   wave 0 draws the token; optionally all waves sweep the rows again to write log-probs
 // Only workgroup barriers separate the steps; nothing crosses workgroups.
-template <int DT, int VEC>
+template <int DT, int VEC, bool GREEDY>
 __global__ __launch_bounds__(kRecThreads) void accept_recover_kernel(const RecArgs a) {
     extern __shared__ double smem_d[];
     __shared__ int sh_n, sh_bad;
     __shared__ double sh_log2Z;
+    __shared__ double sh_best_v[kRecThreads / kWave];
+    __shared__ long sh_best_i[kRecThreads / kWave];
 
     const int b = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -723,20 +770,49 @@ __global__ __launch_bounds__(kRecThreads) void accept_recover_kernel(const RecAr
     // ---- 3
     const long off = (long)b * a.sb + (long)n * a.st;
     const void* g = row_ptr<DT>(a.G, off);
-    const void* sp = row_ptr<DT>(a.Sp, off);
-    const void* sm = row_ptr<DT>(a.Sm, off);
+    const void* sp = row_ptr<DT>(a.recSp, off);
+    const void* sm = row_ptr<DT>(a.recSm, off);
     const long nvec = V / VEC;
     const int tailc = V - (int)(nvec * VEC);
     const long nch = (nvec + kWave * kChunkSteps - 1) / (kWave * kChunkSteps);
+    Best best{-__builtin_huge_val(), 0x7FFFFFFFFFFFFFFFl};
     for (int c = wave; c < a.NC; c += NW) {
-        const Partial p = chunk_mass<DT, VEC>(g, sp, sm, nvec, tailc, nch, c, lane, a.c, a.bc);
+        const Partial p = chunk_mass<DT, VEC, GREEDY>(g, sp, sm, nvec, tailc, nch, c, lane, a.c, a.bc, a.beta, best);
         if (lane == 0) tab[c] = p;
+    }
+    if (GREEDY) {  // best of the wave: larger value, then lower index
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const double ov = __shfl_xor(best.v, d, kWave);
+            const long oi = __shfl_xor(best.idx, d, kWave);
+            if (ov > best.v || (ov == best.v && oi < best.idx)) {
+                best.v = ov;
+                best.idx = oi;
+            }
+        }
+        if (lane == 0) {
+            sh_best_v[wave] = best.v;
+            sh_best_i[wave] = best.idx;
+        }
     }
     __syncthreads();
 
     // ---- 4
     if (wave == 0) {
-        const double log2Z = sample_wave<DT, VEC>(a, b, n, lane, tab, g, sp, sm, nvec, tailc, nch);
+        if (GREEDY) {
+            best.v = lane < NW ? sh_best_v[lane] : -__builtin_huge_val();
+            best.idx = lane < NW ? sh_best_i[lane] : 0x7FFFFFFFFFFFFFFFl;
+#pragma unroll
+            for (int d = 1; d < NW; d <<= 1) {
+                const double ov = __shfl_xor(best.v, d, kWave);
+                const long oi = __shfl_xor(best.idx, d, kWave);
+                if (ov > best.v || (ov == best.v && oi < best.idx)) {
+                    best.v = ov;
+                    best.idx = oi;
+                }
+            }
+        }
+        const double log2Z = sample_wave<DT, VEC, GREEDY>(a, b, n, lane, tab, g, sp, sm, nvec, tailc, nch, best);
         if (lane == 0) sh_log2Z = log2Z;
     }
     if (a.recovery_logprobs) {
@@ -852,7 +928,10 @@ hipError_t launch_all(LseArgs la, RecArgs ra, hipStream_t stream, hipEvent_t* ev
     // accept + recover: LDS holds the per-position log-probs and one mass per recovery chunk
     ra.NC = chunks_per_row(V, VEC);
     const size_t smem = (size_t)2 * kmax * sizeof(double) + (size_t)ra.NC * sizeof(Partial);
-    hipLaunchKernelGGL((accept_recover_kernel<DT, VEC>), dim3((unsigned)B), dim3(kRecThreads), smem, stream, ra);
+    if (ra.greedy)
+        hipLaunchKernelGGL((accept_recover_kernel<DT, VEC, true>), dim3((unsigned)B), dim3(kRecThreads), smem, stream, ra);
+    else
+        hipLaunchKernelGGL((accept_recover_kernel<DT, VEC, false>), dim3((unsigned)B), dim3(kRecThreads), smem, stream, ra);
     if (ev) hipEventRecord(ev[3], stream);
     return hipGetLastError();
 }
@@ -870,7 +949,7 @@ ss_status verify_block_impl(const void* G, const void* S_ctx, const void* S_noct
     if (!(params->lambda > 0.f) || !std::isfinite(params->lambda)) return SS_ERR_PARAM;
     if (!(params->temperature > 0.f) || !std::isfinite(params->temperature)) return SS_ERR_PARAM;
     if (!std::isfinite(params->beta)) return SS_ERR_PARAM;
-    if (params->flags != 0) return SS_ERR_PARAM;
+    if ((params->flags & ~(uint32_t)SS_FLAG_GREEDY) != 0) return SS_ERR_PARAM;
     const long V = params->vocab;
     if (params->stride_t < 0 || params->stride_b < 0) return SS_ERR_STRIDE;
     const long st = params->stride_t ? params->stride_t : V;
@@ -899,7 +978,8 @@ ss_status verify_block_impl(const void* G, const void* S_ctx, const void* S_noct
     la.NS = pl.NS; la.slice_vecs = pl.slice_vecs; la.list_in_lds = 0; la.c_hi = c_hi;
 
     RecArgs ra;
-    ra.G = G; ra.Sp = S_ctx; ra.Sm = S_noctx; ra.draft = draft; ra.draft_len = draft_len; ra.uniforms = uniforms;
+    const bool steer = params->beta != 0.f;
+    ra.G = G; ra.Sm = S_noctx; ra.recSp = steer ? S_ctx : G; ra.recSm = steer ? S_noctx : G; ra.draft = draft; ra.draft_len = draft_len; ra.uniforms = uniforms;
     ra.row_off = la.row_off; ra.partial = la.partial;
     ra.accepted_len = accepted_len; ra.next_token = next_token;
     ra.next_token_logprob = next_token_logprob; ra.recovery_logprobs = recovery_logprobs;
@@ -907,6 +987,8 @@ ss_status verify_block_impl(const void* G, const void* S_ctx, const void* S_noct
     ra.V = params->vocab; ra.NS = pl.NS; ra.NC = 0; ra.c = c;
     ra.bc = (double)params->beta * c; ra.ln_lambda = std::log((double)params->lambda);
     ra.rho = (c - (double)c_hi) / (double)c_hi;
+    ra.beta = (double)params->beta;
+    ra.greedy = (params->flags & SS_FLAG_GREEDY) ? 1 : 0;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t err;

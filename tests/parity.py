@@ -19,7 +19,8 @@ def _np(x):
     return None if x is None else x.detach().cpu().numpy()
 
 
-def oracle_run(oracle, inp, *, lam, beta, temperature, seqs=None, want_recovery_logprobs=True, num_threads=8):
+def oracle_run(oracle, inp, *, lam, beta, temperature, seqs=None, want_recovery_logprobs=True, num_threads=8,
+               greedy=False):
     """Run the oracle on host copies of the inputs (optionally only on sequences ``seqs``)."""
     sel = slice(None) if seqs is None else seqs
     dl = inp.get("draft_len")
@@ -27,7 +28,7 @@ def oracle_run(oracle, inp, *, lam, beta, temperature, seqs=None, want_recovery_
         inp["G"][sel].cpu(), inp["S_ctx"][sel].cpu(), inp["S_noctx"][sel].cpu(), inp["draft"][sel].cpu(),
         inp["uniforms"][sel].cpu(), lam=lam, beta=beta, temperature=temperature,
         draft_len=None if dl is None else dl[sel].cpu(), want_recovery_logprobs=want_recovery_logprobs,
-        num_threads=num_threads)
+        num_threads=num_threads, greedy=greedy)
 
 
 def compare(gpu_out, ora, uniforms, draft_len=None, seqs=None):

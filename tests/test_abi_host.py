@@ -106,7 +106,7 @@ def test_argument_errors_are_reported_on_the_host(B):
     p.dtype = 2
     assert call(B, p) == DTYPE
     for kw in (dict(lam=0.0), dict(lam=-1.0), dict(lam=float("inf")), dict(lam=float("nan")),
-               dict(temperature=0.0), dict(temperature=float("nan")), dict(beta=float("inf")), dict(flags=1)):
+               dict(temperature=0.0), dict(temperature=float("nan")), dict(beta=float("inf")), dict(flags=2), dict(flags=0x80000001)):
         assert call(B, P(**kw)) == PARAM, kw
     assert call(B, P(stride_t=999)) == STRIDE       # rows would overlap
     assert call(B, P(stride_t=1000, stride_b=4999)) == STRIDE

@@ -225,3 +225,102 @@ def test_sampling_edges_on_gpu(binding, oracle):
                                torch.zeros(B, 0, dtype=torch.int32, device="cuda"),
                                torch.tensor(us, dtype=torch.float32, device="cuda").view(B, 1))
     assert out["next_token"].cpu().tolist() == want
+
+
+# ------------------------------------------------------------------ greedy decoding and the comparison modes
+
+@pytest.mark.parametrize("name,batch,vocab", [("c2", 8, 151936), ("c4", 48, 50000), ("c5", 16, 64000), ("c1", 3, 32000)])
+def test_greedy_mode(binding, oracle, name, batch, vocab):
+    w = W.scaled(W.WORKLOADS[name], batch=batch, vocab=vocab, name=f"greedy-{name}")
+    inp = W.generate(w, "cuda")
+    out = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], lam=w.lam,
+                               beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"],
+                               want_recovery_logprobs=True, want_draft_logprobs=True, greedy=True)
+    ora = parity.oracle_run(oracle, inp, lam=w.lam, beta=w.beta, temperature=w.temperature, greedy=True, num_threads=16)
+    rep = parity.compare(out, ora, inp["uniforms"], inp["draft_len"])
+    print(f"\n[{w.name}] {rep}", flush=True)
+    assert rep["near_threshold_samples"] == 0  # no uniform is involved in the pick: nothing is excused there
+    # and the pick does not depend on the sampling uniform
+    inp["uniforms"][:, -1] = 0.123
+    again = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], lam=w.lam,
+                                 beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"], greedy=True)
+    assert torch.equal(out["next_token"], again["next_token"])
+
+
+def test_greedy_ties_take_the_lowest_index_on_gpu(binding):
+    V = 5000
+    G = torch.zeros(4, 1, V, dtype=torch.bfloat16, device="cuda")
+    G[0, 0, [17, 4000, 4999]] = 2.0
+    G[1, 0, [4095, 4096]] = 1.0       # a tie across two lanes / chunks
+    G[2, 0, :] = -3.0                 # everything ties: index 0
+    G[3, 0, 4999] = 0.5
+    z = torch.zeros_like(G)
+    out = binding.verify_block(G, z, z, torch.zeros(4, 0, dtype=torch.int32, device="cuda"),
+                               torch.full((4, 1), 0.9, device="cuda"), greedy=True)
+    assert out["next_token"].cpu().tolist() == [17, 4095, 0, 4999]
+
+
+def test_beta_zero_never_reads_the_context_rows(binding, oracle):
+    w = W.scaled(W.WORKLOADS["c4"], batch=12, vocab=30000, k_max=6, name="beta0")
+    import dataclasses
+    w = dataclasses.replace(w, beta=0.0)
+    inp = W.generate(w, "cuda")
+    ora = parity.oracle_run(oracle, inp, lam=w.lam, beta=0.0, temperature=w.temperature)
+    inp["S_ctx"].fill_(float("nan"))
+    out = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], lam=w.lam,
+                               beta=0.0, temperature=w.temperature, draft_len=inp["draft_len"],
+                               want_recovery_logprobs=True, want_draft_logprobs=True)
+    parity.compare(out, ora, inp["uniforms"], inp["draft_len"])
+
+
+def test_standard_speculative_acceptance_mode(binding, oracle):
+    """The baseline the paper compares with: alpha = min(1, P_LLM / P_SLM^+), no steering.  It is this block
+    with the drafter's own logits in the S_noctx slot, lambda = 1 and beta = 0."""
+    w = W.scaled(W.WORKLOADS["c2"], batch=16, vocab=40000, k_max=8, name="stdspec")
+    inp = W.generate(w, "cuda")
+    out = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_ctx"], inp["draft"], inp["uniforms"], lam=1.0, beta=0.0,
+                               temperature=1.0, want_recovery_logprobs=True, want_draft_logprobs=True)
+    ora = oracle.verify_block(inp["G"].cpu(), inp["S_ctx"].cpu(), inp["S_ctx"].cpu(), inp["draft"].cpu(),
+                              inp["uniforms"].cpu(), lam=1.0, beta=0.0, temperature=1.0, num_threads=16)
+    parity.compare(out, ora, inp["uniforms"], None)
+    # independent check of the rule itself on the GPU's own log-probs
+    lp = out["draft_logprobs"].double().cpu()
+    alpha = torch.exp(lp[..., 0] - lp[..., 1]).clamp(max=1.0)
+    acc = inp["uniforms"].cpu()[:, :8].double() <= alpha
+    n = torch.where(acc.all(1), torch.tensor(8), (~acc).int().argmax(1))
+    assert torch.equal(n.int(), out["accepted_len"].cpu())
+
+
+def test_always_on_steering_rows(binding, oracle):
+    """Eq. 8 and one draw on EVERY row (the per-token fusion baseline): k_max = 0 on flattened rows."""
+    w = W.scaled(W.WORKLOADS["c3"], batch=6, vocab=30000, k_max=7, name="steer-rows")
+    inp = W.generate(w, "cuda")
+    rows = lambda t: t.reshape(-1, w.vocab)
+    G, Sp, Sm = rows(inp["G"]), rows(inp["S_ctx"]), rows(inp["S_noctx"])
+    u = torch.rand(G.shape[0], generator=torch.Generator("cuda").manual_seed(5), device="cuda")
+    out = binding.steer_rows(G, Sp, Sm, u, beta=w.beta, temperature=w.temperature, want_logprobs=True)
+    N = G.shape[0]
+    ora = oracle.verify_block(G.view(N, 1, -1).cpu(), Sp.view(N, 1, -1).cpu(), Sm.view(N, 1, -1).cpu(),
+                              torch.zeros(N, 0, dtype=torch.int32), u.view(N, 1).cpu(), beta=w.beta,
+                              temperature=w.temperature, num_threads=16)
+    rep = parity.compare({"accepted_len": torch.zeros(N, dtype=torch.int32), "next_token": out["token"],
+                          "next_token_logprob": out["token_logprob"], "recovery_logprobs": out["logprobs"]},
+                         ora, u.view(N, 1), None)
+    assert rep["unexcused_mismatches"] == 0
+
+
+def test_draft_sampler_reproduces_the_harness_drafts(binding):
+    """Eq. 5: y ~ softmax(S_ctx / T).  The workload generator draws its drafts with torch (float64 softmax,
+    cumsum, searchsorted); the block with k_max = 0 and beta = 0, fed the same uniforms, must pick the same
+    tokens wherever the uniform is not within 1e-6 of a CDF edge."""
+    w = W.scaled(W.WORKLOADS["c4"], batch=8, vocab=128256, k_max=8, name="drafts")
+    dev = torch.device("cuda")
+    S = (torch.randn(w.batch * w.k_max, w.vocab, generator=torch.Generator(dev).manual_seed(7), device=dev) * 3).to(torch.bfloat16)
+    u64 = torch.rand(S.shape[0], 1, generator=torch.Generator(dev).manual_seed(8), device=dev, dtype=torch.float64)
+    u = u64.float()
+    cdf = torch.cumsum(torch.softmax(S.double() / w.temperature, -1), -1)
+    want = torch.searchsorted(cdf, u.double(), right=True).squeeze(-1).clamp(max=w.vocab - 1)
+    got = binding.sample_rows(S, u.squeeze(-1), temperature=w.temperature)["token"].long()
+    edge = (cdf - u.double()).abs().min(-1).values < 1e-6
+    assert torch.equal(got[~edge], want[~edge])
+    assert (~edge).sum() > 0.8 * len(edge)

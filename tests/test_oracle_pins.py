@@ -445,3 +445,38 @@ def test_golden_rational_examples(oracle):
         for t, a in enumerate(c["alpha"]):
             assert r["alpha"][0, t] == pytest.approx(a, rel=1e-6), c["name"]  # float32 logs of integers
         assert np.allclose(np.exp(r["recovery_logprobs"][0]), c["recovery_probs"], rtol=1e-6), c["name"]
+
+
+# ---------------------------------------------------------------- greedy decoding (the paper's evaluation setting)
+
+def test_greedy_takes_argmax_of_recovery_logits(oracle):
+    """The paper decodes greedily in its experiments; the deterministic form of "Sample y ~ Softmax(h_rec)"
+    is the mode of that distribution: argmax of Eq. 8, independent of temperature and of the sampling uniform."""
+    rng = np.random.default_rng(21)
+    G, Sp, Sm, d, u = rand_block(rng, 16, 3, 90)
+    for beta, T in ((1.0, 1.0), (0.5, 0.7), (2.0, 3.0), (0.0, 1.0)):
+        r = oracle.verify_block(G, Sp, Sm, d, u, beta=beta, temperature=T, greedy=True)
+        rs = oracle.verify_block(G, Sp, Sm, d, u, beta=beta, temperature=T, greedy=False)
+        assert np.array_equal(r["accepted_len"], rs["accepted_len"])  # the ratio test is untouched
+        assert np.array_equal(r["recovery_logprobs"], rs["recovery_logprobs"])
+        n = r["accepted_len"]
+        ar = np.arange(16)
+        # mode of the recovery distribution, from the independently pinned log-probs
+        assert np.array_equal(r["next_token"], np.argmax(rs["recovery_logprobs"], axis=-1))
+        h = G[ar, n].astype(np.float64) + float(np.float32(beta)) * (Sp[ar, n].astype(np.float64) - Sm[ar, n].astype(np.float64))
+        assert np.array_equal(r["next_token"], np.argmax(h, axis=-1))
+        assert np.allclose(r["next_token_logprob"], rs["recovery_logprobs"][ar, r["next_token"]], atol=0)
+        u2 = u.copy()
+        u2[:, -1] = rng.random(16).astype(np.float32)
+        assert np.array_equal(r["next_token"], oracle.verify_block(G, Sp, Sm, d, u2, beta=beta, temperature=T, greedy=True)["next_token"])
+
+
+def test_greedy_ties_go_to_the_lowest_index(oracle):
+    G = np.array([[[1.0, 3.0, 3.0, -1.0, 3.0]]], np.float32)
+    z = np.zeros_like(G)
+    r = oracle.verify_block(G, z, z, np.zeros((1, 0), np.int32), np.array([[0.99]], np.float32), greedy=True)
+    assert r["next_token"][0] == 1
+    # steering breaks the tie: beta * (S_ctx - S_noctx) lifts index 4
+    Sp = np.array([[[0, 0, 0, 0, 0.5]]], np.float32)
+    r = oracle.verify_block(G, Sp, z, np.zeros((1, 0), np.int32), np.array([[0.0]], np.float32), greedy=True, beta=1.0)
+    assert r["next_token"][0] == 4
