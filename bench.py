@@ -52,6 +52,10 @@ def main() -> int:
     ap.add_argument("--sets", type=int, default=2, help="rotating input sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--lam", type=float, default=None, help="override the verification threshold")
+    ap.add_argument("--mode", default="verify", choices=["verify", "greedy", "steer_rows", "draft_sample"],
+                    help="verify: the block (default, the headline metric); greedy: same with argmax recovery; "
+                         "steer_rows: always-on steering, Eq. 8 + one draw on every row of the workload; "
+                         "draft_sample: softmax sampling of every S_ctx row (the drafting step)")
     ap.add_argument("--dense", action="store_true", help="ignore the length array of a ragged workload (K_b = k_max)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device copies (reference for scaling rocprofv3 byte counters)")
@@ -81,8 +85,22 @@ def main() -> int:
         for s_ in sets:
             s_["draft_len"] = None
     B, kmax, V = w.batch, w.k_max, w.vocab
-    params = binding.make_params(B, kmax, V, W.torch_dtype(w.dtype), lam=w.lam, beta=w.beta,
-                                 temperature=w.temperature)
+    rows_mode = args.mode in ("steer_rows", "draft_sample")
+    if rows_mode:
+        # every row of the workload becomes a one-row sequence with no drafted position
+        for s_ in sets:
+            n_rows = B * (kmax + 1)
+            for k_ in ("G", "S_ctx", "S_noctx"):
+                s_[k_] = s_[k_].view(n_rows, 1, V)
+            if args.mode == "draft_sample":
+                s_["G"] = s_["S_noctx"] = s_["S_ctx"]
+            s_["draft"] = torch.empty(n_rows, 0, dtype=torch.int32, device=dev)
+            s_["draft_len"] = None
+            s_["uniforms"] = s_["uniforms"].reshape(n_rows, 1)
+        B, kmax = B * (kmax + 1), 0
+    params = binding.make_params(B, kmax, V, W.torch_dtype(w.dtype), lam=w.lam,
+                                 beta=0.0 if args.mode == "draft_sample" else w.beta, temperature=w.temperature,
+                                 flags=binding.SS_FLAG_GREEDY if args.mode == "greedy" else 0)
     ws = torch.empty(max(256, binding.workspace_bytes(params)), dtype=torch.uint8, device=dev)
     acc = torch.empty(B, dtype=torch.int32, device=dev)
     tok = torch.empty(B, dtype=torch.int32, device=dev)
@@ -93,7 +111,7 @@ def main() -> int:
         return binding.verify_block_raw(s["G"], s["S_ctx"], s["S_noctx"], s["draft"], s["draft_len"], s["uniforms"],
                                         params, acc, tok, tlp, None, None, ws, timed=timed)
 
-    positions = [int(s["draft_len"].sum().item()) if s["draft_len"] is not None else B * kmax for s in sets]
+    positions = [int(s["draft_len"].sum().item()) if s["draft_len"] is not None else B * max(kmax, 1) for s in sets]
 
     if args.calibrate_copy:
         # a plain elementwise copy of known size: reads 1 GiB, writes 1 GiB per launch
@@ -135,11 +153,16 @@ def main() -> int:
         step_bytes += (2.0 * positions[i % len(sets)] + B + 2.0 * n_bonus) * V * esz / n_timed
         bonus_frac += n_bonus / B / n_timed
     lse_gbs = lse_bytes / (stage["row_lse"] * 1e-3) / 1e9 if stage["row_lse"] > 0 else 0.0
+    if rows_mode:
+        # no row pass: the recovery sweep is the dominant (only) kernel; it reads 3 rows per row, 1 when beta = 0
+        per_row = (1 if args.mode == "draft_sample" else 3) * V * esz
+        lse_bytes = step_bytes = float(B) * per_row
+        lse_gbs = lse_bytes / (stage["recover"] * 1e-3) / 1e9
 
     out = {
-        "metric": "verified draft positions/sec",
+        "metric": "verified draft positions/sec" if not rows_mode else "sampled rows/sec",
         "value": pos_total / elapsed,
-        "unit": "positions/s",
+        "unit": "positions/s" if not rows_mode else "rows/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
@@ -149,19 +172,22 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": describe(w), "logits_dtype": w.dtype, "input_sets": len(sets),
+        "config": {"workload": describe(w), "mode": args.mode, "logits_dtype": w.dtype, "input_sets": len(sets),
                    "positions_per_step": positions[0], "bonus_fraction": round(bonus_frac, 4)},
         "roofline": {
-            "bound": "hbm", "kernel": "row_lse_kernel", "achieved": lse_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": lse_gbs / HBM_PEAK_GBS, "traffic": read_traffic(w.name),
-            "algorithmic_bytes_per_launch": lse_bytes, "avg_launch_ms": stage["row_lse"],
+            "bound": "hbm", "kernel": "accept_recover_kernel" if rows_mode else "row_lse_kernel", "achieved": lse_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": lse_gbs / HBM_PEAK_GBS, "traffic": read_traffic(w.name) if args.mode == "verify" else None,
+            "algorithmic_bytes_per_launch": lse_bytes, "avg_launch_ms": stage["recover" if rows_mode else "row_lse"],
         },
         "stages_ms": {k: round(v, 5) for k, v in stage.items()},
         "whole_step": {"algorithmic_bytes": step_bytes, "GB/s": step_bytes / (ms_per_step * 1e-3) / 1e9,
                        "frac_of_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and rows_mode:
+        print("bench.py: --mode steer_rows / draft_sample report no cpu_baseline (use --no-cpu-baseline to silence)",
+              file=sys.stderr)
+    if not args.no_cpu_baseline and not rows_mode:
         import oracle
         import parity
 
@@ -176,7 +202,7 @@ def main() -> int:
         t1 = time.perf_counter()
         ora = oracle.verify_block(host["G"], host["S_ctx"], host["S_noctx"], host["draft"], host["uniforms"],
                                   lam=w.lam, beta=w.beta, temperature=w.temperature, draft_len=host["draft_len"],
-                                  want_recovery_logprobs=False, num_threads=threads)
+                                  want_recovery_logprobs=False, num_threads=threads, greedy=args.mode == "greedy")
         cpu_s = time.perf_counter() - t1
         cpu_pos = int(host["draft_len"].sum().item()) if host["draft_len"] is not None else nseq * kmax
         out["cpu_baseline"] = {

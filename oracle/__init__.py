@@ -56,6 +56,10 @@ def _load():
         lib.specsteer_oracle_verify_block.restype = ctypes.c_int
         lib.specsteer_oracle_verify_block.argtypes = [ctypes.c_void_p] * 14
         lib.specsteer_oracle_max_threads.restype = ctypes.c_int
+        lib.specsteer_oracle_cloud_topk.restype = ctypes.c_int
+        lib.specsteer_oracle_cloud_topk.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int32] + [ctypes.c_void_p] * 2
+        lib.specsteer_oracle_edge_resample.restype = ctypes.c_int
+        lib.specsteer_oracle_edge_resample.argtypes = [ctypes.c_void_p] * 6 + [ctypes.c_int32] + [ctypes.c_void_p] * 4
         _lib = lib
     return _lib
 
@@ -136,3 +140,50 @@ def verify_block(G, S_ctx, S_noctx, draft, uniforms, *, lam=0.5, beta=1.0, tempe
         "alpha": alpha,
         "sample_margin": margin,
     }
+
+
+def _cptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def cloud_topk(G, S_noctx, row, *, beta=1.0, topk=32):
+    """Cloud side of the deployment split: top-k of h_LLM - beta*h_SLM^- at row[b] of every sequence.
+    Returns (index [B, topk] int32, value [B, topk] float32), ordered by decreasing value, ties by id."""
+    g, dt = _logits_array(G)
+    sm, dt2 = _logits_array(S_noctx)
+    if dt != dt2 or g.shape != sm.shape or g.ndim != 3:
+        raise ValueError("logit tensors must share dtype and [B, k_max+1, V] shape")
+    B, k1, V = g.shape
+    r = _int32(row).reshape(B)
+    p = _Params(B, k1 - 1, V, dt, 0, 0, 0.5, float(beta), 1.0, 1, 0)
+    idx = np.empty((B, topk), np.int32)
+    val = np.empty((B, topk), np.float32)
+    rc = _load().specsteer_oracle_cloud_topk(_cptr(g), _cptr(sm), _cptr(r), ctypes.cast(ctypes.byref(p), ctypes.c_void_p),
+                                             int(topk), _cptr(idx), _cptr(val))
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    return idx, val
+
+
+def edge_resample(index, value, S_ctx, row, uniform, *, beta=1.0, temperature=1.0, greedy=False):
+    """Edge side: add beta*h_SLM^+ on the top-k entries and resample among them."""
+    sp, dt = _logits_array(S_ctx)
+    B, k1, V = sp.shape
+    idx = np.ascontiguousarray(index, np.int32)
+    val = np.ascontiguousarray(value, np.float32)
+    topk = idx.shape[1]
+    r = _int32(row).reshape(B)
+    if hasattr(uniform, "detach"):
+        uniform = uniform.detach().cpu().numpy()
+    u = np.ascontiguousarray(uniform, np.float32).reshape(B)
+    p = _Params(B, k1 - 1, V, dt, 0, 0, 0.5, float(beta), float(temperature), 1, 1 if greedy else 0)
+    tok = np.empty(B, np.int32)
+    lp = np.empty(B, np.float64)
+    cand = np.empty((B, topk), np.float64)
+    margin = np.empty(B, np.float64)
+    rc = _load().specsteer_oracle_edge_resample(_cptr(idx), _cptr(val), _cptr(sp), _cptr(r), _cptr(u),
+                                                ctypes.cast(ctypes.byref(p), ctypes.c_void_p), int(topk), _cptr(tok),
+                                                _cptr(lp), _cptr(cand), _cptr(margin))
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    return {"next_token": tok, "next_token_logprob": lp, "cand_logprobs": cand, "sample_margin": margin}

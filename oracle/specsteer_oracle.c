@@ -254,3 +254,129 @@ int specsteer_oracle_max_threads(void) {
     return 1;
 #endif
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Deployment split of the recovery step (appendix "System Deployment", item "Minimal Downlink").
+ *
+ * Cloud side: at the rejected row the non-private part of Eq. 8,
+ *     h_cloud = h_LLM - beta * h_SLM^-,
+ * is truncated to its top-k entries (k = 32 in the paper).  Edge side: the private term is added
+ * back on those entries, h_rec = h_cloud + beta * h_SLM^+, and the token is resampled locally.
+ *
+ * Readings where the paper is silent: entries are ordered by decreasing h_cloud, ties by
+ * increasing token id; the payload carries fp32 values; a token outside the top-k has
+ * probability zero; the edge draws by inverse CDF in payload order (or takes the first maximum
+ * when greedy); if V < k the unused slots hold id -1 and value -inf.
+ * ------------------------------------------------------------------------------------------ */
+
+typedef struct {
+    double v;
+    int32_t idx;
+} sso_entry;
+
+static int entry_before(const void *pa, const void *pb) {
+    const sso_entry *a = (const sso_entry *)pa, *b = (const sso_entry *)pb;
+    if (a->v > b->v) return -1;
+    if (a->v < b->v) return 1;
+    return (a->idx > b->idx) - (a->idx < b->idx);
+}
+
+/*
+ * Host pointers.  row[b] in [0, k_max] selects the row of sequence b; a negative row marks a
+ * flagged sequence (all ids -1, values -inf).  out_index [B, topk] int32, out_value [B, topk] fp32.
+ * Only batch, k_max, vocab, dtype, strides and beta of the params are used.
+ */
+int specsteer_oracle_cloud_topk(const void *G, const void *S_noctx, const int32_t *row, const sso_params *p,
+                                int32_t topk, int32_t *out_index, float *out_value) {
+    if (!G || !S_noctx || !row || !p || !out_index || !out_value || topk < 1) return 1;
+    const int B = p->batch, V = p->vocab, kmax = p->k_max, dt = p->dtype;
+    const int64_t st = p->stride_t ? p->stride_t : (int64_t)V;
+    const int64_t sb = p->stride_b ? p->stride_b : (int64_t)(kmax + 1) * st;
+    const double beta = (double)p->beta;
+    sso_entry *e = (sso_entry *)malloc((size_t)V * sizeof(sso_entry));
+    for (int b = 0; b < B; ++b) {
+        int32_t *oi = out_index + (size_t)b * topk;
+        float *ov = out_value + (size_t)b * topk;
+        for (int j = 0; j < topk; ++j) {
+            oi[j] = -1;
+            ov[j] = -INFINITY;
+        }
+        if (row[b] < 0 || row[b] > kmax) continue;
+        const int64_t off = (int64_t)b * sb + (int64_t)row[b] * st;
+        for (int v = 0; v < V; ++v) {
+            e[v].v = widen(G, dt, off + v) - beta * widen(S_noctx, dt, off + v);
+            e[v].idx = v;
+        }
+        qsort(e, (size_t)V, sizeof(sso_entry), entry_before);
+        for (int j = 0; j < topk && j < V; ++j) {
+            oi[j] = e[j].idx;
+            ov[j] = (float)e[j].v;
+        }
+    }
+    free(e);
+    return 0;
+}
+
+/*
+ * Host pointers.  index/value [B, topk] as produced above, S_ctx [B, k_max+1, V], row [B],
+ * uniform [B] fp32.  Outputs next_token [B] (-1 for a flagged sequence), next_token_logprob [B]
+ * (log-softmax over the top-k candidates), cand_logprobs [B, topk] or NULL, sample_margin [B] or NULL.
+ * Uses batch, k_max, vocab, dtype, strides, beta, temperature and greedy of the params.
+ */
+int specsteer_oracle_edge_resample(const int32_t *index, const float *value, const void *S_ctx, const int32_t *row,
+                                   const float *uniform, const sso_params *p, int32_t topk, int32_t *next_token,
+                                   double *next_token_logprob, double *cand_logprobs, double *sample_margin) {
+    if (!index || !value || !S_ctx || !row || !uniform || !p || !next_token || topk < 1) return 1;
+    const int B = p->batch, V = p->vocab, kmax = p->k_max, dt = p->dtype;
+    const int64_t st = p->stride_t ? p->stride_t : (int64_t)V;
+    const int64_t sb = p->stride_b ? p->stride_b : (int64_t)(kmax + 1) * st;
+    const double beta = (double)p->beta, T = (double)p->temperature;
+    double *h = (double *)malloc((size_t)topk * sizeof(double));
+    for (int b = 0; b < B; ++b) {
+        const int32_t *ix = index + (size_t)b * topk;
+        const float *vl = value + (size_t)b * topk;
+        int n = 0;
+        while (n < topk && ix[n] >= 0) ++n; /* valid candidates are a prefix */
+        if (cand_logprobs)
+            for (int j = 0; j < topk; ++j) cand_logprobs[(size_t)b * topk + j] = -INFINITY;
+        if (row[b] < 0 || row[b] > kmax || n == 0) {
+            next_token[b] = -1;
+            if (next_token_logprob) next_token_logprob[b] = NAN;
+            if (sample_margin) sample_margin[b] = NAN;
+            continue;
+        }
+        const int64_t off = (int64_t)b * sb + (int64_t)row[b] * st;
+        int amax = 0;
+        for (int j = 0; j < n; ++j) {
+            h[j] = (double)vl[j] + beta * widen(S_ctx, dt, off + ix[j]); /* edge adds its private term */
+            if (h[j] > h[amax]) amax = j;
+        }
+        double hs[64];
+        double *x = topk <= 64 ? hs : (double *)malloc((size_t)topk * sizeof(double));
+        for (int j = 0; j < n; ++j) x[j] = h[j] / T;
+        const double lse = log_sum_exp(x, n);
+        double c = 0.0, margin = INFINITY;
+        int pick = -1, last_pos = -1;
+        for (int j = 0; j < n; ++j) {
+            const double lp = x[j] - lse;
+            if (cand_logprobs) cand_logprobs[(size_t)b * topk + j] = lp;
+            const double pj = exp(lp);
+            c += pj;
+            if (pj > 0.0) last_pos = j;
+            if (pick < 0 && c > (double)uniform[b]) pick = j;
+            const double d = fabs(c - (double)uniform[b]);
+            if (d < margin) margin = d;
+        }
+        if (pick < 0) pick = last_pos;
+        if (p->greedy) {
+            pick = amax;
+            margin = INFINITY;
+        }
+        next_token[b] = ix[pick];
+        if (next_token_logprob) next_token_logprob[b] = x[pick] - lse;
+        if (sample_margin) sample_margin[b] = margin;
+        if (x != hs) free(x);
+    }
+    free(h);
+    return 0;
+}

@@ -480,3 +480,65 @@ def test_greedy_ties_go_to_the_lowest_index(oracle):
     Sp = np.array([[[0, 0, 0, 0, 0.5]]], np.float32)
     r = oracle.verify_block(G, Sp, z, np.zeros((1, 0), np.int32), np.array([[0.0]], np.float32), greedy=True, beta=1.0)
     assert r["next_token"][0] == 4
+
+
+# ---------------------------------------------------------------- deployment split: cloud top-k, edge resample
+
+def test_cloud_topk_matches_a_library_sort(oracle):
+    rng = np.random.default_rng(31)
+    G, Sp, Sm, d, u = rand_block(rng, 5, 2, 300)
+    G[0, 1, 7] = G[0, 1, 3] = G[0, 1, 250] = 9.0  # ties inside the top-k
+    Sm[0, 1, [3, 7, 250]] = 0.0
+    row = np.array([1, 0, 2, 1, -1], np.int32)
+    beta = 0.8
+    idx, val = oracle.cloud_topk(G, Sm, row, beta=beta, topk=32)
+    for b in range(4):
+        h = G[b, row[b]].astype(np.float64) - float(np.float32(beta)) * Sm[b, row[b]].astype(np.float64)
+        order = np.lexsort((np.arange(300), -h))[:32]  # by decreasing value, then increasing id
+        assert np.array_equal(idx[b], order)
+        assert np.array_equal(val[b], h[order].astype(np.float32))
+    assert list(idx[0][:3]) == [3, 7, 250]
+    assert np.all(idx[4] == -1) and np.all(np.isneginf(val[4]))
+    # fewer tokens than slots
+    idx, val = oracle.cloud_topk(G[:, :, :5].copy(), Sm[:, :, :5].copy(), row, beta=beta, topk=8)
+    assert np.all(idx[0, 5:] == -1) and np.all(idx[0, :5] >= 0) and sorted(idx[0, :5]) == [0, 1, 2, 3, 4]
+
+
+def test_split_recovery_with_full_payload_equals_eq8(oracle):
+    """h_cloud + beta*h^+ = h_LLM + beta*(h^+ - h^-): with k = V nothing is truncated, so the edge's
+    distribution must be the recovery distribution of the one-GPU block (up to the fp32 payload)."""
+    rng = np.random.default_rng(32)
+    B, V = 6, 40
+    G, Sp, Sm, d, u = rand_block(rng, B, 2, V, scale=1.5)
+    u[:, :2] = 0.0
+    ref = oracle.verify_block(G, Sp, Sm, d, u, beta=1.3, temperature=0.8)  # all accepted: row 2
+    row = ref["accepted_len"]
+    idx, val = oracle.cloud_topk(G, Sm, row, beta=1.3, topk=V)
+    e = oracle.edge_resample(idx, val, Sp, row, u[:, 2], beta=1.3, temperature=0.8)
+    for b in range(B):
+        assert np.allclose(e["cand_logprobs"][b], ref["recovery_logprobs"][b, idx[b]], atol=5e-6)
+        assert np.isclose(np.exp(e["cand_logprobs"][b]).sum(), 1.0, atol=1e-12)
+
+
+def test_edge_resample_law_and_truncation(oracle):
+    """Tokens outside the payload are never drawn; inside it the draw follows softmax over the k candidates:
+    every CDF interval is probed from both sides."""
+    rng = np.random.default_rng(33)
+    V, k = 50, 6
+    G, Sp, Sm, _, _ = rand_block(rng, 1, 0, V, scale=1.0)
+    row = np.zeros(1, np.int32)
+    idx, val = oracle.cloud_topk(G, Sm, row, beta=0.7, topk=k)
+    h = val[0].astype(np.float64) + float(np.float32(0.7)) * Sp[0, 0, idx[0]].astype(np.float64)
+    pr = softmax(h / float(np.float32(1.5)))
+    cdf = np.cumsum(pr)
+    probes = [(0.0, 0)] + [(float(np.float32(cdf[j] - 1e-5)), j) for j in range(k)] + \
+             [(float(np.float32(cdf[j] + 1e-5)), j + 1) for j in range(k - 1)]
+    for us, want in probes:
+        e = oracle.edge_resample(idx, val, Sp, row, np.array([us], np.float32), beta=0.7, temperature=1.5)
+        assert e["next_token"][0] == idx[0, want]
+        assert e["next_token_logprob"][0] == pytest.approx(np.log(pr[want]), abs=1e-12)
+    e = oracle.edge_resample(idx, val, Sp, row, np.array([0.3], np.float32), beta=0.7, temperature=1.5, greedy=True)
+    assert e["next_token"][0] == idx[0, int(np.argmax(h))]
+    # flagged sequence
+    e = oracle.edge_resample(idx, val, Sp, np.array([-1], np.int32), np.array([0.3], np.float32))
+    assert e["next_token"][0] == -1 and np.isnan(e["next_token_logprob"][0])
