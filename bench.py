@@ -43,6 +43,57 @@ def read_traffic(workload: str):
     return None
 
 
+def bench_split(args, w, sets, dev) -> int:
+    """Deployment split: cloud top-k at one (seeded) row per sequence, then the edge resampling."""
+    import torch
+
+    from paper_2603_16219_amd import binding
+
+    B, V = w.batch, w.vocab
+    esz = 2 if w.dtype == "bf16" else 4
+    rows = [torch.randint(0, w.k_max + 1, (B,), generator=torch.Generator(dev).manual_seed(11 + i), device=dev,
+                          dtype=torch.int32) for i in range(len(sets))]
+    us = [s["uniforms"][:, -1].contiguous() for s in sets]
+
+    def step(i):
+        s = sets[i % len(sets)]
+        idx, val = binding.cloud_topk(s["G"], s["S_noctx"], rows[i % len(sets)], beta=w.beta, topk=32)
+        return binding.edge_resample(idx, val, s["S_ctx"], rows[i % len(sets)], us[i % len(sets)], beta=w.beta,
+                                     temperature=w.temperature)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    # the cloud kernel alone, torch events on the current stream (the library launches there)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n_timed = min(args.steps, 20)
+    kms = 0.0
+    for i in range(n_timed):
+        s = sets[i % len(sets)]
+        e0.record()
+        binding.cloud_topk(s["G"], s["S_noctx"], rows[i % len(sets)], beta=w.beta, topk=32)
+        e1.record()
+        e1.synchronize()
+        kms += e0.elapsed_time(e1) / n_timed
+    nbytes = 2.0 * B * V * esz
+    out = {
+        "metric": "top-32 downlink rows/sec", "value": B / (ms * 1e-3), "unit": "rows/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": describe(w), "mode": "cloud_topk", "topk": 32, "logits_dtype": w.dtype},
+        "roofline": {"bound": "hbm", "kernel": "cloud_topk_kernel", "achieved": nbytes / (kms * 1e-3) / 1e9,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": nbytes / (kms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "traffic": None, "algorithmic_bytes_per_launch": nbytes, "avg_launch_ms": kms},
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -52,10 +103,12 @@ def main() -> int:
     ap.add_argument("--sets", type=int, default=2, help="rotating input sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--lam", type=float, default=None, help="override the verification threshold")
-    ap.add_argument("--mode", default="verify", choices=["verify", "greedy", "steer_rows", "draft_sample"],
+    ap.add_argument("--mode", default="verify", choices=["verify", "greedy", "steer_rows", "draft_sample", "cloud_topk"],
                     help="verify: the block (default, the headline metric); greedy: same with argmax recovery; "
                          "steer_rows: always-on steering, Eq. 8 + one draw on every row of the workload; "
-                         "draft_sample: softmax sampling of every S_ctx row (the drafting step)")
+                         "draft_sample: softmax sampling of every S_ctx row (the drafting step); "
+                         "cloud_topk: the deployment split, top-32 of h_LLM - beta*h_SLM^- at one row per sequence "
+                         "followed by the edge-side resampling")
     ap.add_argument("--dense", action="store_true", help="ignore the length array of a ragged workload (K_b = k_max)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device copies (reference for scaling rocprofv3 byte counters)")
@@ -85,6 +138,8 @@ def main() -> int:
         for s_ in sets:
             s_["draft_len"] = None
     B, kmax, V = w.batch, w.k_max, w.vocab
+    if args.mode == "cloud_topk":
+        return bench_split(args, w, sets, dev)
     rows_mode = args.mode in ("steer_rows", "draft_sample")
     if rows_mode:
         # every row of the workload becomes a one-row sequence with no drafted position

@@ -156,6 +156,44 @@ ss_status specsteer_verify_block_timed(const void *G, const void *S_ctx, const v
                                        float *draft_logprobs, void *workspace,
                                        size_t workspace_bytes, void *stream, float *stage_ms);
 
+/*
+ * Deployment split of the recovery step (the paper's appendix on system deployment, "Minimal
+ * Downlink"): the cloud holds h_LLM and h_SLM^-, the edge holds h_SLM^+, and on a rejection only a
+ * sparse top-k vector travels down.
+ *
+ * specsteer_cloud_topk -- cloud side.  For every sequence b, at row row[b] of G and S_noctx:
+ *     h_cloud(v) = h_LLM(v) - beta * h_SLM^-(v)          (the non-private part of Eq. 8)
+ * evaluated in double as one rounded product and one rounded difference, and its topk largest
+ * entries written in order of decreasing h_cloud, ties by increasing token id:
+ *   out_index  device, [B, topk] int32 token ids; -1 in slots beyond the vocabulary (V < topk)
+ *   out_value  device, [B, topk] fp32  h_cloud of those tokens rounded to fp32; -inf in unused slots
+ *   row        device, [B] int32 in [0, k_max] (normally accepted_len of specsteer_verify_block);
+ *              a negative or too large entry marks a flagged sequence: all ids -1, values -inf.
+ * Uses batch, k_max, vocab, dtype, strides, beta of params (host); 1 <= topk <= SS_MAX_TOPK
+ * (the paper uses 32).  No workspace.  Argument errors as for specsteer_verify_block.
+ *
+ * specsteer_edge_resample -- edge side.  For every sequence, on the payload entries j:
+ *     h_rec(j) = value[j] + beta * h_SLM^+(index[j])     (Eq. 8 restricted to the payload)
+ * in double; tokens outside the payload have probability zero (the paper does not say; nothing
+ * else can be computed from the payload); next_token is drawn from Softmax(h_rec / T) over the
+ * payload by inverse CDF in payload order from uniform[b] (first j whose inclusive cumulative
+ * probability exceeds it), or is the first maximum of h_rec with SS_FLAG_GREEDY (uniform may
+ * then be NULL).  next_token_logprob (optional) is the log-probability under that k-way softmax.
+ *   index, value  device, [B, topk] as written by specsteer_cloud_topk
+ *   S_ctx         device, [B, k_max+1, V] logits of params->dtype; only the payload's tokens are read
+ *   row, uniform  device, [B]
+ *   next_token    device, [B] out; -1 (and NaN log-prob) for a flagged sequence or an empty payload
+ * Uses batch, k_max, vocab, dtype, strides, beta, temperature, flags of params.
+ */
+#define SS_MAX_TOPK 64
+ss_status specsteer_cloud_topk(const void *G, const void *S_noctx, const int32_t *row,
+                               const ss_params *params, int32_t topk, int32_t *out_index,
+                               float *out_value, void *stream);
+ss_status specsteer_edge_resample(const int32_t *index, const float *value, const void *S_ctx,
+                                  const int32_t *row, const float *uniform,
+                                  const ss_params *params, int32_t topk, int32_t *next_token,
+                                  float *next_token_logprob, void *stream);
+
 /* Static, human-readable name of an ss_status value. */
 const char *specsteer_status_string(int status);
 

@@ -59,6 +59,12 @@ def library() -> ctypes.CDLL:
             + [ctypes.c_size_t, ctypes.c_void_p])
         lib.specsteer_verify_block_timed.restype = ctypes.c_int
         lib.specsteer_verify_block_timed.argtypes = lib.specsteer_verify_block.argtypes + [ctypes.c_void_p]
+        lib.specsteer_cloud_topk.restype = ctypes.c_int
+        lib.specsteer_cloud_topk.argtypes = ([ctypes.c_void_p] * 3 + [ctypes.POINTER(SSParams), ctypes.c_int32]
+                                             + [ctypes.c_void_p] * 3)
+        lib.specsteer_edge_resample.restype = ctypes.c_int
+        lib.specsteer_edge_resample.argtypes = ([ctypes.c_void_p] * 5 + [ctypes.POINTER(SSParams), ctypes.c_int32]
+                                                + [ctypes.c_void_p] * 3)
         lib.specsteer_status_string.restype = ctypes.c_char_p
         lib.specsteer_status_string.argtypes = [ctypes.c_int]
         lib.specsteer_version.restype = ctypes.c_int
@@ -179,3 +185,48 @@ def sample_rows(logits: torch.Tensor, uniforms: torch.Tensor, *, temperature: fl
     """Plain softmax sampling of [N, V] rows by inverse CDF (Eq. 5, the drafting step, when the rows are
     the specialist's): the block with k_max = 0 and beta = 0, which reads each row once."""
     return steer_rows(logits, logits, logits, uniforms, beta=0.0, temperature=temperature, greedy=greedy)
+
+
+def _split_params(T: torch.Tensor, beta: float, temperature: float, greedy: bool) -> SSParams:
+    B, k1, V = T.shape
+    return make_params(B, k1 - 1, V, T.dtype, lam=0.5, beta=beta, temperature=temperature,
+                       stride_b=T.stride(0) if B > 1 else 0, stride_t=T.stride(1) if k1 > 1 else 0,
+                       flags=SS_FLAG_GREEDY if greedy else 0)
+
+
+def cloud_topk(G: torch.Tensor, S_noctx: torch.Tensor, row: torch.Tensor, *, beta: float = 1.0,
+               topk: int = 32):
+    """specsteer_cloud_topk on device tensors: returns (index [B, topk] int32, value [B, topk] float32)."""
+    if not G.is_cuda or G.shape != S_noctx.shape or G.stride() != S_noctx.stride() or G.stride(2) != 1:
+        raise ValueError("G and S_noctx must be device tensors of one [B, k_max+1, V] shape and stride")
+    B = G.shape[0]
+    row = row.to(device=G.device, dtype=torch.int32).contiguous()
+    idx = torch.empty(B, topk, dtype=torch.int32, device=G.device)
+    val = torch.empty(B, topk, dtype=torch.float32, device=G.device)
+    p = _split_params(G, beta, 1.0, False)
+    rc = library().specsteer_cloud_topk(_ptr(G), _ptr(S_noctx), _ptr(row), ctypes.byref(p), topk, _ptr(idx), _ptr(val),
+                                        ctypes.c_void_p(torch.cuda.current_stream(G.device).cuda_stream))
+    if rc != _STATUS_OK:
+        raise SpecSteerError(rc, status_string(rc))
+    return idx, val
+
+
+def edge_resample(index: torch.Tensor, value: torch.Tensor, S_ctx: torch.Tensor, row: torch.Tensor,
+                  uniform: torch.Tensor, *, beta: float = 1.0, temperature: float = 1.0,
+                  greedy: bool = False) -> dict:
+    """specsteer_edge_resample on device tensors."""
+    if not S_ctx.is_cuda or S_ctx.stride(2) != 1:
+        raise ValueError("S_ctx must be a device tensor with the vocabulary contiguous")
+    B = S_ctx.shape[0]
+    dev = S_ctx.device
+    row = row.to(device=dev, dtype=torch.int32).contiguous()
+    uniform = uniform.to(device=dev, dtype=torch.float32).contiguous()
+    tok = torch.empty(B, dtype=torch.int32, device=dev)
+    lp = torch.empty(B, dtype=torch.float32, device=dev)
+    p = _split_params(S_ctx, beta, temperature, greedy)
+    rc = library().specsteer_edge_resample(_ptr(index.contiguous()), _ptr(value.contiguous()), _ptr(S_ctx), _ptr(row),
+                                           _ptr(uniform), ctypes.byref(p), index.shape[1], _ptr(tok), _ptr(lp),
+                                           ctypes.c_void_p(torch.cuda.current_stream(dev).cuda_stream))
+    if rc != _STATUS_OK:
+        raise SpecSteerError(rc, status_string(rc))
+    return {"next_token": tok, "next_token_logprob": lp}

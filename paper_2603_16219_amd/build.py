@@ -6,7 +6,7 @@ import subprocess
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
-SOURCE = os.path.join(_PKG, "csrc", "specsteer.hip")
+SOURCES = [os.path.join(_PKG, "csrc", n) for n in ("specsteer.hip", "split.hip")]
 INCLUDE = os.path.join(_ROOT, "include")
 LIBRARY = os.path.join(_PKG, "libspecsteer.so")
 
@@ -20,7 +20,7 @@ HIPCC_FLAGS = [
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", INCLUDE, "-o", LIBRARY, SOURCE]
+    cmd = [hipcc, *HIPCC_FLAGS, "-I", INCLUDE, "-o", LIBRARY, *SOURCES]
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, capture_output=True, text=True)

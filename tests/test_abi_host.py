@@ -32,8 +32,9 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol(lib):
     names = declared_symbols()
-    assert names == ["specsteer_status_string", "specsteer_verify_block", "specsteer_verify_block_timed",
-                     "specsteer_version", "specsteer_workspace_bytes"]
+    assert names == ["specsteer_cloud_topk", "specsteer_edge_resample", "specsteer_status_string",
+                     "specsteer_verify_block", "specsteer_verify_block_timed", "specsteer_version",
+                     "specsteer_workspace_bytes"]
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -123,3 +124,24 @@ def test_python_wrapper_refuses_cpu_tensors(B):
     x = torch.zeros(1, 2, 8)
     with pytest.raises(ValueError):
         B.verify_block(x, x, x, torch.zeros(1, 1, dtype=torch.int32), torch.zeros(1, 2))
+
+
+def test_split_entry_points_reject_bad_arguments_on_the_host(B):
+    import torch
+
+    lib = B.library()
+    P = lambda **kw: B.make_params(kw.get("batch", 0), 4, kw.get("vocab", 1000), torch.bfloat16, lam=0.5,
+                                   beta=kw.get("beta", 1.0), temperature=kw.get("temperature", 1.0),
+                                   flags=kw.get("flags", 0))
+    f = lambda x: ctypes.c_void_p(x)
+    cloud = lambda p, topk=32, g=4096: lib.specsteer_cloud_topk(f(g), f(8192), f(12288), ctypes.byref(p), topk,
+                                                                f(16384), f(20480), None)
+    edge = lambda p, topk=32, u=4096: lib.specsteer_edge_resample(f(4096), f(8192), f(12288), f(16384), f(u),
+                                                                  ctypes.byref(p), topk, f(20480), f(24576), None)
+    assert cloud(P()) == 0 and edge(P()) == 0               # batch == 0: validated, nothing launched
+    assert cloud(P(), topk=0) == 2 and cloud(P(), topk=65) == 2 and edge(P(), topk=0) == 2
+    assert cloud(P(), g=0) == 1 and edge(P(), u=0) == 1
+    assert edge(P(flags=1), u=0) == 0                       # greedy needs no uniform
+    assert cloud(P(beta=float("nan"))) == 4 and edge(P(temperature=0.0)) == 4 and cloud(P(flags=4)) == 4
+    assert cloud(P(vocab=0)) == 2
+    assert lib.specsteer_cloud_topk(f(1), f(1), f(1), None, 32, f(1), f(1), None) == 1

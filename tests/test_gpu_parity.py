@@ -324,3 +324,70 @@ def test_draft_sampler_reproduces_the_harness_drafts(binding):
     edge = (cdf - u.double()).abs().min(-1).values < 1e-6
     assert torch.equal(got[~edge], want[~edge])
     assert (~edge).sum() > 0.8 * len(edge)
+
+
+# ------------------------------------------------------------------ deployment split: cloud top-k, edge resample
+
+def _split_case(binding, oracle, w, topk, greedy=False, pad=0):
+    inp = W.generate(w, "cuda")
+    if pad:
+        for k in ("G", "S_ctx", "S_noctx"):
+            inp[k][..., w.vocab - pad:] = float("nan")
+            inp[k] = inp[k][..., : w.vocab - pad]
+    B = w.batch
+    row = torch.randint(0, w.k_max + 1, (B,), generator=torch.Generator("cuda").manual_seed(3), device="cuda",
+                        dtype=torch.int32)
+    if B > 2:
+        row[1] = -1  # a flagged sequence
+    idx, val = binding.cloud_topk(inp["G"], inp["S_noctx"], row, beta=w.beta, topk=topk)
+    oidx, oval = oracle.cloud_topk(inp["G"].cpu(), inp["S_noctx"].cpu(), row.cpu(), beta=w.beta, topk=topk)
+    assert np.array_equal(idx.cpu().numpy(), oidx), "payload ids differ"
+    assert np.array_equal(val.cpu().numpy(), oval), "payload values differ"
+    u = inp["uniforms"][:, -1].contiguous()
+    out = binding.edge_resample(idx, val, inp["S_ctx"], row, u, beta=w.beta, temperature=w.temperature, greedy=greedy)
+    ora = oracle.edge_resample(oidx, oval, inp["S_ctx"].cpu(), row.cpu(), u.cpu(), beta=w.beta,
+                               temperature=w.temperature, greedy=greedy)
+    tok = out["next_token"].cpu().numpy()
+    lp = out["next_token_logprob"].cpu().numpy().astype(np.float64)
+    excused = ora["sample_margin"] < parity.NEAR
+    mism = tok != ora["next_token"]
+    assert not np.any(mism & ~excused), (tok, ora["next_token"])
+    ok = ~mism & (ora["next_token"] >= 0)
+    assert np.all(np.abs(lp[ok] - ora["next_token_logprob"][ok]) <= 1e-5 + 2.0 ** -24 * np.abs(ora["next_token_logprob"][ok]))
+    assert np.all(np.isnan(lp[ora["next_token"] < 0]))
+    print(f"\n[{w.name}] split ok: {int(excused.sum())} near-threshold, {int((mism & excused).sum())} excused mismatches", flush=True)
+
+
+@pytest.mark.parametrize("name,batch,vocab,topk", [("c4", 24, 128256, 32), ("c2", 8, 151936, 32), ("c5", 8, 50000, 64),
+                                                    ("c3", 6, 20011, 32), ("c1", 2, 32000, 32), ("c4", 5, 777, 5),
+                                                    ("c4", 4, 20, 32), ("c4", 3, 1, 1)])
+def test_cloud_topk_and_edge_resample(binding, oracle, name, batch, vocab, topk):
+    w = W.scaled(W.WORKLOADS[name], batch=batch, vocab=vocab, k_max=min(W.WORKLOADS[name].k_max, 4),
+                 name=f"split-{name}-{vocab}-{topk}")
+    _split_case(binding, oracle, w, topk)
+    _split_case(binding, oracle, w, topk, greedy=True)
+
+
+def test_cloud_topk_with_ties_and_padded_rows(binding, oracle):
+    w = W.scaled(W.WORKLOADS["c4"], batch=4, vocab=4103 + 9, k_max=2, name="split-pad")
+    _split_case(binding, oracle, w, 32, pad=9)  # stride 4112 (aligned rows), V = 4103: partial last vector
+    # many exact ties: quantised logits
+    inp = W.generate(W.scaled(W.WORKLOADS["c4"], batch=3, vocab=9000, k_max=1, name="ties"), "cuda")
+    for k in ("G", "S_noctx"):
+        inp[k] = (inp[k].float().round() * 0.5).to(torch.bfloat16)
+    row = torch.zeros(3, dtype=torch.int32, device="cuda")
+    idx, val = binding.cloud_topk(inp["G"], inp["S_noctx"], row, beta=0.5, topk=32)
+    oidx, oval = oracle.cloud_topk(inp["G"].cpu(), inp["S_noctx"].cpu(), row.cpu(), beta=0.5, topk=32)
+    assert np.array_equal(idx.cpu().numpy(), oidx) and np.array_equal(val.cpu().numpy(), oval)
+
+
+def test_full_payload_reproduces_the_one_gpu_recovery(binding):
+    """k = V (tiny vocabulary): the split loses nothing, so its token must be the block's token."""
+    w = W.scaled(W.WORKLOADS["c2"], batch=32, vocab=48, k_max=3, name="split-full")
+    inp = W.generate(w, "cuda")
+    ref = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], lam=w.lam,
+                               beta=w.beta, temperature=w.temperature, greedy=True)
+    idx, val = binding.cloud_topk(inp["G"], inp["S_noctx"], ref["accepted_len"], beta=w.beta, topk=48)
+    out = binding.edge_resample(idx, val, inp["S_ctx"], ref["accepted_len"], inp["uniforms"][:, -1].contiguous(),
+                                beta=w.beta, temperature=w.temperature, greedy=True)
+    assert torch.equal(out["next_token"], ref["next_token"])
