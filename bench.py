@@ -109,6 +109,8 @@ def main() -> int:
                          "draft_sample: softmax sampling of every S_ctx row (the drafting step); "
                          "cloud_topk: the deployment split, top-32 of h_LLM - beta*h_SLM^- at one row per sequence "
                          "followed by the edge-side resampling")
+    ap.add_argument("--full-rows", action="store_true",
+                    help="one-pass schedule: score every valid row even after a sequence's first rejection")
     ap.add_argument("--dense", action="store_true", help="ignore the length array of a ragged workload (K_b = k_max)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device copies (reference for scaling rocprofv3 byte counters)")
@@ -155,7 +157,9 @@ def main() -> int:
         B, kmax = B * (kmax + 1), 0
     params = binding.make_params(B, kmax, V, W.torch_dtype(w.dtype), lam=w.lam,
                                  beta=0.0 if args.mode == "draft_sample" else w.beta, temperature=w.temperature,
-                                 flags=binding.SS_FLAG_GREEDY if args.mode == "greedy" else 0)
+                                 flags=(binding.SS_FLAG_GREEDY if args.mode == "greedy" else 0)
+                                 | (binding.SS_FLAG_FULL_ROWS if args.full_rows else 0))
+    t1 = binding.first_window(params)
     ws = torch.empty(max(256, binding.workspace_bytes(params)), dtype=torch.uint8, device=dev)
     acc = torch.empty(B, dtype=torch.int32, device=dev)
     tok = torch.empty(B, dtype=torch.int32, device=dev)
@@ -194,6 +198,7 @@ def main() -> int:
     lse_bytes = 0.0
     step_bytes = 0.0
     bonus_frac = 0.0
+    rows_scored = 0.0
     for i in range(n_timed):
         ms = step(i, timed=True)
         for k in stage:
@@ -201,13 +206,19 @@ def main() -> int:
         s = sets[i % len(sets)]
         K = s["draft_len"] if s["draft_len"] is not None else torch.full((B,), kmax, dtype=torch.int32, device=dev)
         n_bonus = int((acc == K).sum().item())
-        # row pass: two rows of V logits per verified position
-        lse_bytes += 2.0 * positions[i % len(sets)] * V * esz / n_timed
-        # whole step, unique bytes: the row pass, the S_ctx recovery row of every sequence, and the
-        # G / S_noctx bonus rows of fully accepted sequences (a rejected row was already read by the row pass)
-        step_bytes += (2.0 * positions[i % len(sets)] + B + 2.0 * n_bonus) * V * esz / n_timed
+        # rows the schedule scores: the first window for everyone, the rest for sequences not rejected inside it
+        in_play = (K > t1) & (acc >= t1)
+        rows = int(torch.clamp(K, max=t1).sum().item()) + int((K - t1)[in_play].sum().item())
+        rows_scored += rows / n_timed
+        # row pass: two rows of V logits per scored position
+        lse_bytes += 2.0 * rows * V * esz / n_timed
+        # whole step, unique bytes: the row passes, the S_ctx recovery row of every sequence, and the
+        # G / S_noctx bonus rows of fully accepted sequences (a rejected row was already read by a row pass)
+        step_bytes += (2.0 * rows + B + 2.0 * n_bonus) * V * esz / n_timed
         bonus_frac += n_bonus / B / n_timed
-    lse_gbs = lse_bytes / (stage["row_lse"] * 1e-3) / 1e9 if stage["row_lse"] > 0 else 0.0
+    lse_ms = stage["row_pass1"] + stage["row_pass2"]
+    lse_gbs = lse_bytes / (lse_ms * 1e-3) / 1e9 if lse_ms > 0 else 0.0
+    n_lse = 2 if (not rows_mode and t1 < kmax) else 1  # launches of the row-pass kernel per step
     if rows_mode:
         # no row pass: the recovery sweep is the dominant (only) kernel; it reads 3 rows per row, 1 when beta = 0
         per_row = (1 if args.mode == "draft_sample" else 3) * V * esz
@@ -228,11 +239,13 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": describe(w), "mode": args.mode, "logits_dtype": w.dtype, "input_sets": len(sets),
-                   "positions_per_step": positions[0], "bonus_fraction": round(bonus_frac, 4)},
+                   "positions_per_step": positions[0], "bonus_fraction": round(bonus_frac, 4),
+                   "first_window": t1, "rows_scored_per_step": round(rows_scored, 1)},
         "roofline": {
             "bound": "hbm", "kernel": "accept_recover_kernel" if rows_mode else "row_lse_kernel", "achieved": lse_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": lse_gbs / HBM_PEAK_GBS, "traffic": read_traffic(w.name) if args.mode == "verify" else None,
-            "algorithmic_bytes_per_launch": lse_bytes, "avg_launch_ms": stage["recover" if rows_mode else "row_lse"],
+            "algorithmic_bytes_per_launch": lse_bytes / n_lse, "avg_launch_ms": stage["recover"] if rows_mode else lse_ms / n_lse,
+            "launches_per_step": n_lse,
         },
         "stages_ms": {k: round(v, 5) for k, v in stage.items()},
         "whole_step": {"algorithmic_bytes": step_bytes, "GB/s": step_bytes / (ms_per_step * 1e-3) / 1e9,
@@ -265,11 +278,16 @@ def main() -> int:
             "sample": f"first {nseq} of {B} sequences of {w.name} ({cpu_pos} positions), float64 oracle, "
                       f"{threads} OpenMP threads over sequences, {cpu_s:.2f} s wall",
         }
-        # parity of the same step against the oracle, reported beside the timing
-        dlp = torch.empty(B, kmax, 2, dtype=torch.float32, device=dev)
+        # parity of the same step against the oracle, reported beside the timing: the step as timed, plus a
+        # second call that also asks for the per-position log-probs (which takes the one-pass schedule)
         binding.verify_block_raw(s["G"], s["S_ctx"], s["S_noctx"], s["draft"], s["draft_len"], s["uniforms"], params,
-                                 acc, tok, tlp, None, dlp, ws)
+                                 acc, tok, tlp, None, None, ws)
+        dlp = torch.empty(B, kmax, 2, dtype=torch.float32, device=dev)
+        acc2, tok2, tlp2 = torch.empty_like(acc), torch.empty_like(tok), torch.empty_like(tlp)
+        binding.verify_block_raw(s["G"], s["S_ctx"], s["S_noctx"], s["draft"], s["draft_len"], s["uniforms"], params,
+                                 acc2, tok2, tlp2, None, dlp, ws)
         torch.cuda.synchronize()
+        assert torch.equal(acc, acc2) and torch.equal(tok, tok2), "the two schedules disagree"
         rep = parity.compare({"accepted_len": acc, "next_token": tok, "next_token_logprob": tlp,
                               "draft_logprobs": dlp}, ora, s["uniforms"], s["draft_len"], seqs=seqs)
         out["parity"] = rep

@@ -69,7 +69,7 @@ typedef struct {
     float lambda;        /* verification threshold of Eq. 7; finite, > 0. Paper default 0.5    */
     float beta;          /* steering-recovery strength of Eq. 8; finite. Paper default 1.0     */
     float temperature;   /* T; finite, > 0. 1.0 reproduces the paper                           */
-    uint32_t flags;      /* 0, or SS_FLAG_GREEDY; any other bit is an error                    */
+    uint32_t flags;      /* 0 or a combination of the SS_FLAG_ bits below; any other bit is an error */
 } ss_params;
 
 /*
@@ -80,6 +80,24 @@ typedef struct {
  * h_LLM + beta * (h_SLM^+ - h_SLM^-) in double precision with no fused multiply-add.
  */
 #define SS_FLAG_GREEDY 1u
+
+/*
+ * Algorithm 1 leaves its loop at the first rejection, so the rows of the later positions of a
+ * rejected sequence never need scoring.  On large batches the block therefore scores the first
+ * quarter of the positions for every sequence, applies the ratio test to them, and scores the
+ * remaining positions only for the sequences that have not been rejected yet.  The outputs are
+ * the same; only draft_logprobs (which asks for every position) forces the one-pass schedule.
+ * SS_FLAG_FULL_ROWS forces it too: every valid row of G and S_noctx is then read.
+ */
+#define SS_FLAG_FULL_ROWS 2u
+
+/*
+ * Number of leading positions per sequence that the first row pass of specsteer_verify_block
+ * scores for these params (host call).  Equal to k_max when the block is verified in one pass
+ * (small batches, k_max < 4, SS_FLAG_FULL_ROWS; a non-NULL draft_logprobs has the same effect at
+ * call time).  Returns -1 for invalid params.
+ */
+int specsteer_first_window(const ss_params *params);
 
 /*
  * Bytes of device scratch specsteer_verify_block needs for these params
@@ -138,16 +156,19 @@ ss_status specsteer_verify_block(const void *G, const void *S_ctx, const void *S
  * Eq. 7, Eq. 8; same arguments, same outputs, same errors).  It brackets each kernel with
  * HIP events recorded on `stream`, WAITS for the last one, and writes the elapsed
  * milliseconds of each stage to the host array stage_ms[SS_NUM_STAGES]:
- *   [SS_STAGE_PREP]    ragged row list (0 when draft_len is NULL),
- *   [SS_STAGE_ROW_LSE] the log-sum-exp pass over every valid row of G and S_noctx,
- *   [SS_STAGE_RECOVER] ratio test, first rejection, recovery distribution, sampling and the
- *                      optional log-prob rows.
+ *   [SS_STAGE_ROW_PASS1] log-sum-exp pass over G and S_noctx, positions [0, first window),
+ *   [SS_STAGE_VERDICT]   ratio test on those positions (0 in the one-pass schedule),
+ *   [SS_STAGE_ROW_PASS2] log-sum-exp pass over the remaining positions of the sequences still in
+ *                        play (0 in the one-pass schedule),
+ *   [SS_STAGE_RECOVER]   ratio test, first rejection, recovery distribution, sampling and the
+ *                        optional log-prob rows.
  * Creates and destroys its events inside the call, so it is not for latency-critical use.
  */
-#define SS_STAGE_PREP 0
-#define SS_STAGE_ROW_LSE 1
-#define SS_STAGE_RECOVER 2
-#define SS_NUM_STAGES 3
+#define SS_STAGE_ROW_PASS1 0
+#define SS_STAGE_VERDICT 1
+#define SS_STAGE_ROW_PASS2 2
+#define SS_STAGE_RECOVER 3
+#define SS_NUM_STAGES 4
 ss_status specsteer_verify_block_timed(const void *G, const void *S_ctx, const void *S_noctx,
                                        const int32_t *draft, const int32_t *draft_len,
                                        const float *uniforms, const ss_params *params,

@@ -16,6 +16,7 @@ from . import build as _build
 
 SS_F32, SS_BF16 = 0, 1
 SS_FLAG_GREEDY = 1
+SS_FLAG_FULL_ROWS = 2
 _STATUS_OK = 0
 
 
@@ -65,6 +66,8 @@ def library() -> ctypes.CDLL:
         lib.specsteer_edge_resample.restype = ctypes.c_int
         lib.specsteer_edge_resample.argtypes = ([ctypes.c_void_p] * 5 + [ctypes.POINTER(SSParams), ctypes.c_int32]
                                                 + [ctypes.c_void_p] * 3)
+        lib.specsteer_first_window.restype = ctypes.c_int
+        lib.specsteer_first_window.argtypes = [ctypes.POINTER(SSParams)]
         lib.specsteer_status_string.restype = ctypes.c_char_p
         lib.specsteer_status_string.argtypes = [ctypes.c_int]
         lib.specsteer_version.restype = ctypes.c_int
@@ -88,6 +91,10 @@ def make_params(batch: int, k_max: int, vocab: int, dtype: torch.dtype, *, lam: 
     return SSParams(batch, k_max, vocab, code, stride_b, stride_t, lam, beta, temperature, flags)
 
 
+def first_window(params: SSParams) -> int:
+    return int(library().specsteer_first_window(ctypes.byref(params)))
+
+
 def workspace_bytes(params: SSParams) -> int:
     return int(library().specsteer_workspace_bytes(ctypes.byref(params)))
 
@@ -96,7 +103,7 @@ def _ptr(t: Optional[torch.Tensor]):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
-STAGES = ("prep", "row_lse", "recover")
+STAGES = ("row_pass1", "verdict", "row_pass2", "recover")
 
 
 def verify_block_raw(G, S_ctx, S_noctx, draft, draft_len, uniforms, params: SSParams, accepted_len,
@@ -127,7 +134,7 @@ def verify_block(G: torch.Tensor, S_ctx: torch.Tensor, S_noctx: torch.Tensor, dr
                  uniforms: torch.Tensor, *, lam: float = 0.5, beta: float = 1.0, temperature: float = 1.0,
                  draft_len: Optional[torch.Tensor] = None, want_recovery_logprobs: bool = False,
                  want_draft_logprobs: bool = False, workspace: Optional[torch.Tensor] = None,
-                 greedy: bool = False) -> dict:
+                 greedy: bool = False, full_rows: bool = False) -> dict:
     """specsteer_verify_block on device tensors G/S_ctx/S_noctx [B, k_max+1, V] (vocab stride 1),
     draft [B, k_max] int32, uniforms [B, k_max+1] float32.  Allocates the outputs (and a workspace
     unless one is given) with torch and returns them in a dict; runs on torch's current stream."""
@@ -148,7 +155,7 @@ def verify_block(G: torch.Tensor, S_ctx: torch.Tensor, S_noctx: torch.Tensor, dr
         draft_len = draft_len.to(device=dev, dtype=torch.int32).contiguous()
     params = make_params(B, k_max, V, G.dtype, lam=lam, beta=beta, temperature=temperature,
                          stride_b=G.stride(0) if B > 1 else 0, stride_t=G.stride(1) if k1 > 1 else 0,
-                         flags=SS_FLAG_GREEDY if greedy else 0)
+                         flags=(SS_FLAG_GREEDY if greedy else 0) | (SS_FLAG_FULL_ROWS if full_rows else 0))
     need = workspace_bytes(params)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)

@@ -164,24 +164,36 @@ __device__ __forceinline__ Partial wave_combine(Acc a) {
     return Partial{Em, S};
 }
 
-// ------------------------------------------------------------------ ragged row list
+// ------------------------------------------------------------------ row lists
 
-// off[b] = number of valid (sequence, position) rows before sequence b; off[B] = total.
-// A length outside [0, k_max] contributes no rows (the sequence is flagged later).
+// Which rows a row pass covers: positions [t_lo, t_hi) of every sequence that is still in play.
+// The block is verified in at most two such windows (see the host side): Algorithm 1 stops at the
+// first rejection, so the later positions of a sequence rejected early never need their rows.
+struct RowWindow {
+    const int32_t* draft_len;  // NULL => K_b = k_max
+    const int32_t* alive;      // NULL => every sequence; else rows only where alive[b] != 0
+    int kmax, t_lo, t_hi;
+};
+
+// Rows of sequence b inside the window.  A length outside [0, k_max] contributes none
+// (the sequence is flagged elsewhere).
+__device__ __forceinline__ int window_rows(const RowWindow& w, int b) {
+    const int K = w.draft_len ? w.draft_len[b] : w.kmax;
+    if (K < 0 || K > w.kmax) return 0;
+    if (w.alive && !w.alive[b]) return 0;
+    return max(0, min(K, w.t_hi) - w.t_lo);
+}
+
+// off[b] = number of window rows before sequence b; off[B] = total.
 // Called by every thread of a workgroup of NT threads (NT a multiple of 64, at most 1024);
 // `off` may be LDS or global memory.  Ends with a barrier, so `off` is readable on return.
-__device__ __forceinline__ void block_scan_lengths(const int32_t* __restrict__ draft_len, int B, int kmax,
-                                                   int* off, int NT) {
+__device__ __forceinline__ void block_scan_rows(const RowWindow& win, int B, int* off, int NT) {
     __shared__ int wave_tot[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NW = NT >> 6;
     int carry = 0;
     for (int b0 = 0; b0 < B; b0 += NT) {
         const int b = b0 + tid;
-        int k = 0;
-        if (b < B) {
-            k = draft_len[b];
-            if (k < 0 || k > kmax) k = 0;
-        }
+        const int k = b < B ? window_rows(win, b) : 0;
         int incl = k;
 #pragma unroll
         for (int d = 1; d < kWave; d <<= 1) {
@@ -205,9 +217,8 @@ __device__ __forceinline__ void block_scan_lengths(const int32_t* __restrict__ d
 }
 
 // Only for batches too large for the in-kernel LDS row list.
-__global__ __launch_bounds__(1024) void prep_rows_kernel(const int32_t* __restrict__ draft_len, int B, int kmax,
-                                                         int32_t* __restrict__ row_off) {
-    block_scan_lengths(draft_len, B, kmax, row_off, 1024);
+__global__ __launch_bounds__(1024) void prep_rows_kernel(const RowWindow win, int B, int32_t* __restrict__ row_off) {
+    block_scan_rows(win, B, row_off, 1024);
 }
 
 // ------------------------------------------------------------------ kernel: row log-sum-exp partials
@@ -215,13 +226,14 @@ __global__ __launch_bounds__(1024) void prep_rows_kernel(const int32_t* __restri
 struct LseArgs {
     const void* G;
     const void* Sm;
-    const int32_t* draft_len;  // NULL => every sequence has k_max rows
-    int32_t* row_off;          // ragged: global copy of the row list, [B+1]
+    RowWindow win;             // the rows this launch covers
+    int uniform_rows;          // > 0: every sequence has exactly this many window rows, no list needed
+    int32_t* row_off;          // else: global copy of the row list, [B+1]
     Partial* partial;          // [rows][2][NS]
     long sb, st;               // element strides
     int B, kmax, V, NS;
     int slice_vecs;            // vectors (of the fast path's width) per slice
-    int list_in_lds;           // ragged: build the row list in LDS (else row_off was filled by prep_rows)
+    int list_in_lds;           // build the row list in LDS (else row_off was filled by prep_rows)
     float c_hi;                // fl32(log2(e)/T)
 };
 
@@ -229,22 +241,22 @@ struct LseArgs {
 // of one row.  One wave per item, no communication between waves; the grid is persistent and
 // strides over the item list.  Ragged batches build the row list in LDS at kernel start
 // (every workgroup repeats the same small scan), so no separate launch is needed.
-// Workgroup 0 also publishes the row list for the recovery pass.
+// Workgroup 0 also publishes the row list for the kernels that consume the partials.
 template <int DT, int VEC, int VECFAST, int kUnroll>
 __global__ __launch_bounds__(kLseThreads) void row_lse_kernel(const LseArgs a) {
     extern __shared__ int lds_off[];
     const int lane = threadIdx.x & 63;
     const int wave_global = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (kLseThreads / kWave) + (threadIdx.x >> 6)));
     const int waves_total = gridDim.x * (kLseThreads / kWave);
-    const bool ragged = a.draft_len != nullptr;
+    const bool ragged = a.uniform_rows <= 0;
     const int* off = a.row_off;
     if (ragged && a.list_in_lds) {
-        block_scan_lengths(a.draft_len, a.B, a.kmax, lds_off, kLseThreads);
+        block_scan_rows(a.win, a.B, lds_off, kLseThreads);
         off = lds_off;
     }
     if (blockIdx.x == 0 && ragged && a.list_in_lds)
         for (int i = threadIdx.x; i <= a.B; i += kLseThreads) a.row_off[i] = lds_off[i];
-    const int R = ragged ? off[a.B] : a.B * a.kmax;
+    const int R = ragged ? off[a.B] : a.B * a.uniform_rows;
     const long items = (long)R * 2 * a.NS;
     // a slice is slice_vecs vectors of the fast width; the element-wise path covers the same logits
     const long slice_units = (long)a.slice_vecs * (VECFAST / VEC);
@@ -265,10 +277,10 @@ __global__ __launch_bounds__(kLseThreads) void row_lse_kernel(const LseArgs a) {
                 if (off[mid] <= r) lo = mid; else hi = mid;
             }
             b = lo;
-            t = r - off[b];
+            t = a.win.t_lo + (r - off[b]);
         } else {
-            b = r / a.kmax;
-            t = r - b * a.kmax;
+            b = r / a.uniform_rows;
+            t = a.win.t_lo + (r - b * a.uniform_rows);
         }
         const void* row = row_ptr<DT>(x ? a.Sm : a.G, (long)b * a.sb + (long)t * a.st);
         const long v0 = (long)k * slice_units;
@@ -315,15 +327,25 @@ struct RecArgs {
     const int32_t* draft;
     const int32_t* draft_len;
     const float* uniforms;
-    const int32_t* row_off;  // ragged: [B+1] row list written by the row pass
-    const Partial* partial;  // [rows][2][NS] from the row pass
+    // Partials of positions [0, t1) come from the first row pass, those of [t1, k_max) from the
+    // second (t1 == k_max when there is only one pass).  off1 / off2 are the passes' row lists;
+    // rows1 > 0 means the first pass had that many rows for every sequence and no list.
+    const int32_t* off1;
+    const int32_t* off2;
+    const Partial* partial1;
+    const Partial* partial2;
+    const int32_t* alive;    // two passes: sequences whose later positions were scored; else NULL
+    const int32_t* flagged;  // two passes: bad length or draft id, found by the verdict kernel; else NULL
+    const int32_t* first_rej;  // two passes: first rejection inside the first window (verdict kernel)
+    int t1, rows1;
     int32_t* accepted_len;
     int32_t* next_token;
     float* next_token_logprob;
     float* recovery_logprobs;
     float* draft_logprobs;
     long sb, st;
-    int B, kmax, V, NS;
+    int B, kmax, V;
+    int NS, NS2;     // slices per row in the first / second row pass
     int NC;          // chunks per row (full chunks + one pseudo-chunk for the logits past the last vector)
     double c;        // log2(e) / T
     double bc;       // beta * log2(e) / T
@@ -546,6 +568,96 @@ __device__ __forceinline__ double sample_wave(const RecArgs& a, int b, int n, in
     return log2Z;
 }
 
+// Slice partials of (sequence b, position t, tensor x): from the first row pass for t < t1, from the
+// second for t >= t1.
+__device__ __forceinline__ const Partial* partials_of(const RecArgs& a, int b, int t, int x) {
+    if (t < a.t1) {
+        const long r = (a.rows1 > 0 ? (long)b * a.rows1 : (long)a.off1[b]) + t;
+        return a.partial1 + (r * 2 + x) * a.NS;
+    }
+    const long r = (long)a.off2[b] + (t - a.t1);
+    return a.partial2 + (r * 2 + x) * a.NS2;
+}
+
+// Phase 2 for one sequence by its workgroup of kRecThreads threads, on positions [0, Kt):
+//   2a  every (position, tensor) pair gets a wave: merge its slice partials, gather the draft
+//       token's logit, leave log P(y_t) in lp[2t + x]        (two memory round trips in all)
+//   2b  wave 0: Eq. 7 on every position, first rejection by ballot -> *sh_n (Kt if none)
+// A draft id outside the vocabulary among those positions sets *sh_bad.  Ends with a barrier.
+template <int DT>
+__device__ __forceinline__ void ratio_test_block(const RecArgs& a, int b, int Kt, double* lp, int* sh_n, int* sh_bad) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int NW = kRecThreads / kWave;
+    const int kmax = a.kmax, V = a.V;
+    for (int q = wave; q < 2 * Kt; q += NW) {
+        const int t = q >> 1, x = q & 1;
+        const int y = a.draft[(long)b * kmax + t];  // wave-uniform
+        const bool ok = (y >= 0 && y < V);
+        const long off = (long)b * a.sb + (long)t * a.st;
+        const float h = ok ? ld_elem<DT>(row_ptr<DT>(x ? a.Sm : a.G, off), y) : 0.f;
+        const double L = combine_partials_wave(partials_of(a, b, t, x), t < a.t1 ? a.NS : a.NS2, lane, a.rho);
+        if (lane == 0) {
+            lp[q] = kLn2 * ((double)h * a.c - L);
+            if (!ok) *sh_bad = 1;
+        }
+    }
+    __syncthreads();
+    if (wave == 0) {
+        int first_rej = Kt;
+        for (int t0 = 0; t0 < Kt; t0 += kWave) {
+            const int t = t0 + lane;
+            bool rej = false;
+            if (t < Kt) {
+                const double alpha = fmin(1.0, exp(lp[2 * t] - lp[2 * t + 1] - a.ln_lambda));  // Eq. 7
+                rej = !((double)a.uniforms[(long)b * (kmax + 1) + t] <= alpha);
+            }
+            const unsigned long long rmask = __ballot(rej);
+            if (rmask && first_rej == Kt) first_rej = t0 + first_lane(rmask);
+        }
+        if (lane == 0) *sh_n = first_rej;
+    }
+    __syncthreads();
+}
+
+// Between the two row passes: the ratio test on the positions of the first window,
+// [0, min(K_b, t1)), with exactly the arithmetic of the final kernel.  A sequence rejected there is
+// finished as far as verification goes (Algorithm 1 breaks out of the loop at the first
+// rejection): its later rows are never scored and its first-rejection index is final.  Every
+// draft id of the sequence is range-checked here, so a sequence is flagged exactly as in the
+// one-pass schedule.
+template <int DT>
+__global__ __launch_bounds__(kRecThreads) void verdict_kernel(const RecArgs a, int32_t* alive, int32_t* flagged,
+                                                              int32_t* first_rej) {
+    extern __shared__ double smem_d[];
+    __shared__ int sh_n, sh_bad;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int kmax = a.kmax, V = a.V;
+    const int K = a.draft_len ? a.draft_len[b] : kmax;
+    const bool bad_len = (K < 0 || K > kmax);
+    if (tid == 0) {
+        sh_bad = bad_len ? 1 : 0;
+        sh_n = 0;
+    }
+    __syncthreads();
+    if (!bad_len) {
+        bool oob = false;
+        for (int t = tid; t < K; t += kRecThreads) {
+            const int y = a.draft[(long)b * kmax + t];
+            oob = oob || y < 0 || y >= V;
+        }
+        if (oob) sh_bad = 1;
+    }
+    __syncthreads();
+    const int Kt = sh_bad ? 0 : min(K, a.t1);
+    ratio_test_block<DT>(a, b, Kt, smem_d, &sh_n, &sh_bad);
+    if (tid == 0) {
+        const bool bad = sh_bad != 0;
+        alive[b] = (!bad && sh_n == Kt && K > a.t1) ? 1 : 0;
+        flagged[b] = bad ? 1 : 0;
+        first_rej[b] = sh_n;
+    }
+}
+
 // One workgroup (16 waves) per sequence, everything after the row pass in one launch:
 //   2a  every (position, tensor) pair gets a wave: merge its slice partials, gather the draft
 //       token's logit, leave log P(y_t) in LDS            (two memory round trips in all)
@@ -570,48 +682,23 @@ __global__ __launch_bounds__(kRecThreads) void accept_recover_kernel(const RecAr
     Partial* tab = reinterpret_cast<Partial*>(smem_d + 2 * kmax);   // [NC] chunk masses
 
     const int K = a.draft_len ? a.draft_len[b] : kmax;
-    const bool bad_len = (K < 0 || K > kmax);
-    if (tid == 0) sh_bad = bad_len ? 1 : 0;
-    __syncthreads();
-
-    // ---- 2a
-    if (!bad_len && K > 0) {
-        const long r0 = a.draft_len ? (long)a.row_off[b] : (long)b * kmax;
-        for (int q = wave; q < 2 * K; q += NW) {
-            const int t = q >> 1, x = q & 1;
-            const int y = a.draft[(long)b * kmax + t];  // wave-uniform
-            const bool ok = (y >= 0 && y < V);
-            const long off = (long)b * a.sb + (long)t * a.st;
-            const float h = ok ? ld_elem<DT>(row_ptr<DT>(x ? a.Sm : a.G, off), y) : 0.f;
-            const double L = combine_partials_wave(a.partial + ((r0 + t) * 2 + x) * a.NS, a.NS, lane, a.rho);
-            if (lane == 0) {
-                lp[q] = kLn2 * ((double)h * a.c - L);
-                if (!ok) sh_bad = 1;
-            }
-        }
+    const bool bad_len = (K < 0 || K > kmax) || (a.flagged && a.flagged[b]);
+    // Two-pass schedule: a sequence the verdict kernel saw rejected inside the first window keeps
+    // that first-rejection index (its later rows were never scored); every other sequence has all
+    // of its rows and is tested here over all K positions.
+    const bool settled = a.alive && !a.alive[b] && !bad_len && K > a.t1;
+    const int Kt = bad_len ? 0 : K;
+    if (tid == 0) {
+        sh_bad = bad_len ? 1 : 0;
+        sh_n = settled ? a.first_rej[b] : 0;
     }
     __syncthreads();
+    if (!settled) ratio_test_block<DT>(a, b, Kt, lp, &sh_n, &sh_bad);
     const bool bad = sh_bad != 0;
-
-    // ---- 2b
-    if (wave == 0 && !bad) {
-        int first_rej = K;
-        for (int t0 = 0; t0 < K; t0 += kWave) {
-            const int t = t0 + lane;
-            bool rej = false;
-            if (t < K) {
-                const double alpha = fmin(1.0, exp(lp[2 * t] - lp[2 * t + 1] - a.ln_lambda));  // Eq. 7
-                rej = !((double)a.uniforms[(long)b * (kmax + 1) + t] <= alpha);
-            }
-            const unsigned long long rmask = __ballot(rej);
-            if (rmask && first_rej == K) first_rej = t0 + first_lane(rmask);
-        }
-        if (lane == 0) sh_n = first_rej;
-    }
     if (a.draft_logprobs) {  // valid positions from LDS, padded slots 0, a flagged sequence NaN throughout
         const float nanv = __int_as_float(0x7FC00000);
         for (int i = tid; i < kmax * 2; i += kRecThreads)
-            a.draft_logprobs[(long)b * kmax * 2 + i] = bad ? nanv : (i < 2 * K ? (float)lp[i] : 0.f);
+            a.draft_logprobs[(long)b * kmax * 2 + i] = bad ? nanv : (i < 2 * Kt ? (float)lp[i] : 0.f);
     }
     if (bad) {
         if (tid == 0) {
@@ -696,11 +783,26 @@ __global__ __launch_bounds__(kRecThreads) void accept_recover_kernel(const RecAr
 
 struct Plan {
     int vecfast;     // logits per 16-byte vector
-    int NS;          // slices per row
-    int slice_vecs;  // fast-width vectors per slice
-    size_t off_partial;
+    int NS, slice_vecs;    // first row pass: slices per row, fast-width vectors per slice
+    int NS2, slice_vecs2;  // second row pass
+    int NSf, slice_vecsf;  // one pass over all k_max positions (taken when draft_logprobs is requested)
+    int t1;          // positions in the first row pass; == k_max when the block is verified in one pass
+    size_t off_list2, off_alive, off_flagged, off_firstrej, off_partial;
     size_t bytes;
 };
+
+// Two row passes pay off when the batch is large enough to be bandwidth-bound and long enough for
+// a first rejection to cut rows: the first quarter of the positions is scored for everyone, the
+// rest only for the sequences that are still in play.
+constexpr long kEarlyExitMinBytes = 512l << 20;
+
+int first_window(const ss_params* p) {
+    if (p->flags & SS_FLAG_FULL_ROWS) return p->k_max;
+    if (p->k_max < 4) return p->k_max;
+    const long esz = p->dtype == SS_BF16 ? 2 : 4;
+    if ((long)p->batch * p->k_max * 2 * p->vocab * esz < kEarlyExitMinBytes) return p->k_max;
+    return p->k_max / 4;
+}
 
 bool shape_ok(const ss_params* p) {
     if (!p) return false;
@@ -719,16 +821,13 @@ int chunks_per_row(int V, int vec) {
     return (int)nch + ((V % vec) ? 1 : 0);
 }
 
-// Slices per row: 64 KiB slices for big batches, smaller ones (down to one unrolled group)
-// when there are too few rows to give every resident wave several slices.
-Plan make_plan(const ss_params* p) {
-    Plan pl;
-    pl.vecfast = p->dtype == SS_BF16 ? 8 : 4;
-    const long nvec = (p->vocab + pl.vecfast - 1) / pl.vecfast;
-    const long rows2 = (long)p->batch * p->k_max * 2;
+// Slices per row for a pass expected to cover `row_tensors` (row, tensor) pairs: 64 KiB slices for
+// big passes, smaller ones (down to one unrolled group) when there are too few rows to give every
+// resident wave several slices -- a wave that gets one or two long slices cannot balance.
+void slice_plan(long nvec, long row_tensors, int& NS, int& slice_vecs) {
     long ns_lo = (nvec + kMaxSliceVecs - 1) / kMaxSliceVecs;
     long ns_hi = (nvec + kMinSliceVecs - 1) / kMinSliceVecs;
-    long want = rows2 > 0 ? (32768 + rows2 - 1) / rows2 : 1;
+    long want = row_tensors > 0 ? (32768 + row_tensors - 1) / row_tensors : 1;
     long ns = want < ns_lo ? ns_lo : (want > ns_hi ? ns_hi : want);
     if (ns > kMaxSlices) ns = kMaxSlices;
     if (ns < 1) ns = 1;
@@ -736,48 +835,114 @@ Plan make_plan(const ss_params* p) {
     sv = (sv + kMinSliceVecs - 1) / kMinSliceVecs * kMinSliceVecs;
     ns = (nvec + sv - 1) / sv;
     if (ns < 1) ns = 1;
-    pl.NS = (int)ns;
-    pl.slice_vecs = (int)sv;
+    NS = (int)ns;
+    slice_vecs = (int)sv;
+}
+
+Plan make_plan(const ss_params* p) {
+    Plan pl;
+    pl.vecfast = p->dtype == SS_BF16 ? 8 : 4;
+    const long nvec = (p->vocab + pl.vecfast - 1) / pl.vecfast;
+    pl.t1 = first_window(p);
+    const long rows1 = (long)p->batch * pl.t1, rows2 = (long)p->batch * (p->k_max - pl.t1);
+    slice_plan(nvec, rows1 * 2, pl.NS, pl.slice_vecs);
+    // the second pass covers only the sequences still in play: typically a third of the padded rows
+    slice_plan(nvec, rows2 * 2 / 3, pl.NS2, pl.slice_vecs2);
+    slice_plan(nvec, (long)p->batch * p->k_max * 2, pl.NSf, pl.slice_vecsf);
     const size_t B = (size_t)p->batch;
-    size_t o = align_up((B + 1) * sizeof(int32_t), 256);  // row list of a ragged batch
+    size_t o = align_up((B + 1) * sizeof(int32_t), 256);  // row list of the first pass
+    pl.off_list2 = o;    o += align_up((B + 1) * sizeof(int32_t), 256);      // row list of the second pass
+    pl.off_alive = o;    o += align_up((B ? B : 1) * sizeof(int32_t), 256);
+    pl.off_flagged = o;  o += align_up((B ? B : 1) * sizeof(int32_t), 256);
+    pl.off_firstrej = o; o += align_up((B ? B : 1) * sizeof(int32_t), 256);
     pl.off_partial = o;
-    o += align_up((size_t)(rows2 > 0 ? rows2 : 1) * pl.NS * sizeof(Partial), 256);
+    // sized for the one-pass schedule as well (a call that asks for draft_logprobs takes it): all
+    // k_max positions at the finer of the two slicings
+    size_t ns_max = (size_t)(pl.NS > pl.NS2 ? pl.NS : pl.NS2);
+    if ((size_t)pl.NSf > ns_max) ns_max = (size_t)pl.NSf;
+    o += align_up(((size_t)p->batch * p->k_max * 2 + 1) * ns_max * sizeof(Partial), 256);
     pl.bytes = o;
     return pl;
 }
 
+// One row pass over window `win`.  `uniform_rows` > 0 when every sequence has that many rows.
 template <int DT, int VEC, int VECFAST>
-hipError_t launch_all(LseArgs la, RecArgs ra, hipStream_t stream, hipEvent_t* ev) {
-    const int B = ra.B, kmax = ra.kmax, V = ra.V;
+void launch_row_pass(LseArgs la, const RowWindow& win, int uniform_rows, int32_t* row_off, Partial* partial,
+                     long max_rows, hipStream_t stream) {
+    const int B = la.B;
     const int cus = device_cu_count();
-    const bool ragged = ra.draft_len != nullptr && kmax > 0;
+    la.win = win;
+    la.uniform_rows = uniform_rows;
+    la.row_off = row_off;
+    la.partial = partial;
+    const bool listed = uniform_rows <= 0;
     // the row list is built in LDS by the row pass unless the batch is too large for it
-    const bool global_list = ragged && B > kMaxLdsBatch;
-    la.draft_len = ragged ? ra.draft_len : nullptr;
-    la.list_in_lds = (ragged && !global_list) ? 1 : 0;
-    if (ev) hipEventRecord(ev[0], stream);
-    if (global_list)
-        hipLaunchKernelGGL(prep_rows_kernel, dim3(1), dim3(1024), 0, stream, ra.draft_len, B, kmax, la.row_off);
-    if (ev) hipEventRecord(ev[1], stream);
-    const long items = (long)B * kmax * 2 * la.NS;
-    if (items > 0) {  // row pass
-        const long per_wg = kLseThreads / kWave;
-        long wgs = (items + per_wg - 1) / per_wg;
-        const long cap = (long)cus * kLseWgPerCu;
-        if (wgs > cap) wgs = cap;
-        const size_t lds = la.list_in_lds ? (size_t)(B + 1) * sizeof(int) : 0;
-        hipLaunchKernelGGL((row_lse_kernel<DT, VEC, VECFAST, kLseUnroll>), dim3((unsigned)wgs), dim3(kLseThreads), lds,
-                           stream, la);
+    const bool global_list = listed && B > kMaxLdsBatch;
+    la.list_in_lds = (listed && !global_list) ? 1 : 0;
+    if (global_list) hipLaunchKernelGGL(prep_rows_kernel, dim3(1), dim3(1024), 0, stream, win, B, row_off);
+    const long items = max_rows * 2 * la.NS;
+    if (items <= 0) return;
+    const long per_wg = kLseThreads / kWave;
+    long wgs = (items + per_wg - 1) / per_wg;
+    const long cap = (long)cus * kLseWgPerCu;
+    if (wgs > cap) wgs = cap;
+    const size_t lds = la.list_in_lds ? (size_t)(B + 1) * sizeof(int) : 0;
+    hipLaunchKernelGGL((row_lse_kernel<DT, VEC, VECFAST, kLseUnroll>), dim3((unsigned)wgs), dim3(kLseThreads), lds,
+                       stream, la);
+}
+
+template <int DT, int VEC, int VECFAST>
+hipError_t launch_all(LseArgs la, RecArgs ra, const Plan& pl, char* ws, hipStream_t stream, hipEvent_t* ev) {
+    const int B = ra.B, kmax = ra.kmax, V = ra.V;
+    int32_t* off1 = reinterpret_cast<int32_t*>(ws);
+    int32_t* off2 = reinterpret_cast<int32_t*>(ws + pl.off_list2);
+    int32_t* alive = reinterpret_cast<int32_t*>(ws + pl.off_alive);
+    int32_t* flagged = reinterpret_cast<int32_t*>(ws + pl.off_flagged);
+    int32_t* first_rej = reinterpret_cast<int32_t*>(ws + pl.off_firstrej);
+    Partial* partial1 = reinterpret_cast<Partial*>(ws + pl.off_partial);
+    // the verdict's position-by-position log-probs are only complete in the one-pass schedule
+    const int t1 = ra.draft_logprobs ? kmax : pl.t1;
+    const bool two_pass = t1 < kmax;
+    if (t1 != pl.t1) {  // one pass although the plan was made for two
+        la.NS = pl.NSf;
+        la.slice_vecs = pl.slice_vecsf;
     }
-    if (ev) hipEventRecord(ev[2], stream);
-    // accept + recover: LDS holds the per-position log-probs and one mass per recovery chunk
+    Partial* partial2 = partial1 + (size_t)B * t1 * 2 * la.NS;
+    ra.NS = la.NS;
+    ra.NS2 = pl.NS2;
+    const bool ragged = ra.draft_len != nullptr && kmax > 0;
+
+    ra.t1 = t1;
+    ra.rows1 = ragged ? 0 : t1;
+    ra.off1 = off1; ra.off2 = off2; ra.partial1 = partial1; ra.partial2 = partial2;
+    ra.alive = two_pass ? alive : nullptr;
+    ra.flagged = two_pass ? flagged : nullptr;
+    ra.first_rej = two_pass ? first_rej : nullptr;
     ra.NC = chunks_per_row(V, VEC);
     const size_t smem = (size_t)2 * kmax * sizeof(double) + (size_t)ra.NC * sizeof(Partial);
+
+    if (ev) hipEventRecord(ev[0], stream);
+    if (kmax > 0)
+        launch_row_pass<DT, VEC, VECFAST>(la, RowWindow{ragged ? ra.draft_len : nullptr, nullptr, kmax, 0, t1},
+                                          ragged ? 0 : t1, off1, partial1, (long)B * t1, stream);
+    if (ev) hipEventRecord(ev[1], stream);
+    if (two_pass)
+        hipLaunchKernelGGL((verdict_kernel<DT>), dim3((unsigned)B), dim3(kRecThreads), (size_t)2 * kmax * sizeof(double),
+                           stream, ra, alive, flagged, first_rej);
+    if (ev) hipEventRecord(ev[2], stream);
+    if (two_pass) {
+        la.NS = pl.NS2;
+        la.slice_vecs = pl.slice_vecs2;
+        launch_row_pass<DT, VEC, VECFAST>(la, RowWindow{ra.draft_len, alive, kmax, t1, kmax}, 0, off2, partial2,
+                                          (long)B * (kmax - t1), stream);
+    }
+    if (ev) hipEventRecord(ev[3], stream);
+    // accept + recover: LDS holds the per-position log-probs and one mass per recovery chunk
     if (ra.greedy)
         hipLaunchKernelGGL((accept_recover_kernel<DT, VEC, true>), dim3((unsigned)B), dim3(kRecThreads), smem, stream, ra);
     else
         hipLaunchKernelGGL((accept_recover_kernel<DT, VEC, false>), dim3((unsigned)B), dim3(kRecThreads), smem, stream, ra);
-    if (ev) hipEventRecord(ev[3], stream);
+    if (ev) hipEventRecord(ev[4], stream);
     return hipGetLastError();
 }
 
@@ -794,7 +959,7 @@ ss_status verify_block_impl(const void* G, const void* S_ctx, const void* S_noct
     if (!(params->lambda > 0.f) || !std::isfinite(params->lambda)) return SS_ERR_PARAM;
     if (!(params->temperature > 0.f) || !std::isfinite(params->temperature)) return SS_ERR_PARAM;
     if (!std::isfinite(params->beta)) return SS_ERR_PARAM;
-    if ((params->flags & ~(uint32_t)SS_FLAG_GREEDY) != 0) return SS_ERR_PARAM;
+    if ((params->flags & ~(uint32_t)(SS_FLAG_GREEDY | SS_FLAG_FULL_ROWS)) != 0) return SS_ERR_PARAM;
     const long V = params->vocab;
     if (params->stride_t < 0 || params->stride_b < 0) return SS_ERR_STRIDE;
     const long st = params->stride_t ? params->stride_t : V;
@@ -817,19 +982,18 @@ ss_status verify_block_impl(const void* G, const void* S_ctx, const void* S_noct
     const float c_hi = (float)c;  // the row pass scales by this; the merge repairs the difference
 
     LseArgs la;
-    la.G = G; la.Sm = S_noctx; la.draft_len = draft_len; la.row_off = reinterpret_cast<int32_t*>(ws);
-    la.partial = reinterpret_cast<Partial*>(ws + pl.off_partial);
+    la.G = G; la.Sm = S_noctx; la.row_off = nullptr; la.partial = nullptr; la.uniform_rows = 0;
+    la.win = RowWindow{nullptr, nullptr, params->k_max, 0, params->k_max};
     la.sb = sb; la.st = st; la.B = params->batch; la.kmax = params->k_max; la.V = params->vocab;
     la.NS = pl.NS; la.slice_vecs = pl.slice_vecs; la.list_in_lds = 0; la.c_hi = c_hi;
 
     RecArgs ra;
     const bool steer = params->beta != 0.f;
     ra.G = G; ra.Sm = S_noctx; ra.recSp = steer ? S_ctx : G; ra.recSm = steer ? S_noctx : G; ra.draft = draft; ra.draft_len = draft_len; ra.uniforms = uniforms;
-    ra.row_off = la.row_off; ra.partial = la.partial;
     ra.accepted_len = accepted_len; ra.next_token = next_token;
     ra.next_token_logprob = next_token_logprob; ra.recovery_logprobs = recovery_logprobs;
     ra.draft_logprobs = draft_logprobs; ra.sb = sb; ra.st = st; ra.B = params->batch; ra.kmax = params->k_max;
-    ra.V = params->vocab; ra.NS = pl.NS; ra.NC = 0; ra.c = c;
+    ra.V = params->vocab; ra.NS = pl.NS; ra.NS2 = pl.NS2; ra.NC = 0; ra.c = c;
     ra.bc = (double)params->beta * c; ra.ln_lambda = std::log((double)params->lambda);
     ra.rho = (c - (double)c_hi) / (double)c_hi;
     ra.beta = (double)params->beta;
@@ -838,9 +1002,9 @@ ss_status verify_block_impl(const void* G, const void* S_ctx, const void* S_noct
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t err;
     if (params->dtype == SS_BF16) {
-        err = fast ? launch_all<SS_BF16, 8, 8>(la, ra, s, ev) : launch_all<SS_BF16, 1, 8>(la, ra, s, ev);
+        err = fast ? launch_all<SS_BF16, 8, 8>(la, ra, pl, ws, s, ev) : launch_all<SS_BF16, 1, 8>(la, ra, pl, ws, s, ev);
     } else {
-        err = fast ? launch_all<SS_F32, 4, 4>(la, ra, s, ev) : launch_all<SS_F32, 1, 4>(la, ra, s, ev);
+        err = fast ? launch_all<SS_F32, 4, 4>(la, ra, pl, ws, s, ev) : launch_all<SS_F32, 1, 4>(la, ra, pl, ws, s, ev);
     }
     return err == hipSuccess ? SS_OK : SS_ERR_DEVICE;
 }
@@ -888,6 +1052,11 @@ ss_status specsteer_verify_block_timed(const void* G, const void* S_ctx, const v
     }
     for (int i = 0; i < made; ++i) hipEventDestroy(ev[i]);
     return st;
+}
+
+int specsteer_first_window(const ss_params* params) {
+    if (!shape_ok(params)) return -1;
+    return first_window(params);
 }
 
 const char* specsteer_status_string(int status) {

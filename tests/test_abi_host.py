@@ -32,7 +32,8 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol(lib):
     names = declared_symbols()
-    assert names == ["specsteer_cloud_topk", "specsteer_edge_resample", "specsteer_status_string",
+    assert names == ["specsteer_cloud_topk", "specsteer_edge_resample", "specsteer_first_window",
+                     "specsteer_status_string",
                      "specsteer_verify_block", "specsteer_verify_block_timed", "specsteer_version",
                      "specsteer_workspace_bytes"]
     for n in names:
@@ -107,7 +108,7 @@ def test_argument_errors_are_reported_on_the_host(B):
     p.dtype = 2
     assert call(B, p) == DTYPE
     for kw in (dict(lam=0.0), dict(lam=-1.0), dict(lam=float("inf")), dict(lam=float("nan")),
-               dict(temperature=0.0), dict(temperature=float("nan")), dict(beta=float("inf")), dict(flags=2), dict(flags=0x80000001)):
+               dict(temperature=0.0), dict(temperature=float("nan")), dict(beta=float("inf")), dict(flags=4), dict(flags=0x80000001)):
         assert call(B, P(**kw)) == PARAM, kw
     assert call(B, P(stride_t=999)) == STRIDE       # rows would overlap
     assert call(B, P(stride_t=1000, stride_b=4999)) == STRIDE
@@ -142,6 +143,18 @@ def test_split_entry_points_reject_bad_arguments_on_the_host(B):
     assert cloud(P(), topk=0) == 2 and cloud(P(), topk=65) == 2 and edge(P(), topk=0) == 2
     assert cloud(P(), g=0) == 1 and edge(P(), u=0) == 1
     assert edge(P(flags=1), u=0) == 0                       # greedy needs no uniform
-    assert cloud(P(beta=float("nan"))) == 4 and edge(P(temperature=0.0)) == 4 and cloud(P(flags=4)) == 4
+    assert cloud(P(beta=float("nan"))) == 4 and edge(P(temperature=0.0)) == 4 and cloud(P(flags=8)) == 4
     assert cloud(P(vocab=0)) == 2
     assert lib.specsteer_cloud_topk(f(1), f(1), f(1), None, 32, f(1), f(1), None) == 1
+
+
+def test_first_window(B):
+    import torch
+
+    big = B.make_params(256, 16, 128256, torch.bfloat16, lam=0.5, beta=0.8, temperature=0.7)
+    assert B.first_window(big) == 4
+    big.flags = B.SS_FLAG_FULL_ROWS
+    assert B.first_window(big) == 16
+    assert B.first_window(B.make_params(8, 8, 151936, torch.bfloat16, lam=0.5, beta=1.0, temperature=1.0)) == 8   # small batch
+    assert B.first_window(B.make_params(512, 3, 256000, torch.bfloat16, lam=0.5, beta=1.0, temperature=1.0)) == 3  # short block
+    assert B.first_window(B.make_params(-1, 3, 10, torch.bfloat16, lam=0.5, beta=1.0, temperature=1.0)) == -1

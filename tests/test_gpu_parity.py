@@ -391,3 +391,68 @@ def test_full_payload_reproduces_the_one_gpu_recovery(binding):
     out = binding.edge_resample(idx, val, inp["S_ctx"], ref["accepted_len"], inp["uniforms"][:, -1].contiguous(),
                                 beta=w.beta, temperature=w.temperature, greedy=True)
     assert torch.equal(out["next_token"], ref["next_token"])
+
+
+# ------------------------------------------------------------------ two-pass schedule (stop scoring after a rejection)
+
+@pytest.mark.parametrize("name,batch,vocab", [("c4", 96, 100000), ("c5", 160, 110000), ("c3", 128, 151936)])
+def test_two_pass_schedule_matches_one_pass_and_oracle(binding, oracle, name, batch, vocab):
+    """Large enough for the library to split the row pass in two windows: outputs must equal those of the
+    one-pass schedule bit for bit (same arithmetic, fewer rows read) and match the oracle."""
+    w = W.scaled(W.WORKLOADS[name], batch=batch, vocab=vocab, name=f"twopass-{name}")
+    inp = W.generate(w, "cuda")
+    p = binding.make_params(w.batch, w.k_max, w.vocab, inp["G"].dtype, lam=w.lam, beta=w.beta, temperature=w.temperature)
+    assert binding.first_window(p) == w.k_max // 4, "this case is meant to take the two-pass schedule"
+    kw = dict(lam=w.lam, beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"], want_recovery_logprobs=True)
+    two = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], **kw)
+    one = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], full_rows=True, **kw)
+    for k in ("accepted_len", "next_token", "next_token_logprob", "recovery_logprobs"):
+        assert torch.equal(two[k], one[k]), k
+    ora = parity.oracle_run(oracle, inp, lam=w.lam, beta=w.beta, temperature=w.temperature, num_threads=16)
+    rep = parity.compare(two, ora, inp["uniforms"], inp["draft_len"])
+    print(f"\n[{w.name}] {rep}", flush=True)
+    n = two["accepted_len"].cpu()
+    t1 = w.k_max // 4
+    assert (n < t1).any() and (n >= t1).any(), "both kinds of sequences should occur"
+
+
+def test_two_pass_schedule_never_reads_rows_after_an_early_rejection(binding):
+    w = W.scaled(W.WORKLOADS["c4"], batch=96, vocab=100000, name="twopass-poison")
+    inp = W.generate(w, "cuda")
+    assert binding.first_window(binding.make_params(w.batch, w.k_max, w.vocab, inp["G"].dtype, lam=w.lam, beta=w.beta,
+                                                    temperature=w.temperature)) == w.k_max // 4
+    kw = dict(lam=w.lam, beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"])
+    ref = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], **kw)
+    n = ref["accepted_len"].cpu()
+    L = inp["draft_len"].cpu()
+    t1 = w.k_max // 4
+    poisoned = 0
+    for b in range(w.batch):
+        if n[b] < t1 and L[b] > t1:  # rejected inside the first window: rows t1.. are dead weight
+            for k in ("G", "S_noctx"):
+                inp[k][b, t1:] = float("nan")
+            poisoned += 1
+    assert poisoned > 5
+    got = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], **kw)
+    for k in ("accepted_len", "next_token", "next_token_logprob"):
+        assert torch.equal(ref[k], got[k]), k
+
+
+def test_two_pass_schedule_flags_bad_sequences_like_one_pass(binding, oracle):
+    w = W.scaled(W.WORKLOADS["c4"], batch=96, vocab=100000, name="twopass-bad")
+    inp = W.generate(w, "cuda")
+    assert binding.first_window(binding.make_params(w.batch, w.k_max, w.vocab, inp["G"].dtype, lam=w.lam, beta=w.beta,
+                                                    temperature=w.temperature)) == w.k_max // 4
+    inp["draft_len"][3] = 17
+    inp["draft_len"][4] = -2
+    inp["draft_len"][5] = 16
+    inp["draft"][5, 15] = 100000    # out of vocabulary far behind any likely rejection
+    inp["draft_len"][6] = 2
+    inp["draft"][6, 1] = -1
+    inp["draft_len"][7] = 0
+    out = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], lam=w.lam,
+                               beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"])
+    ora = parity.oracle_run(oracle, inp, lam=w.lam, beta=w.beta, temperature=w.temperature, want_recovery_logprobs=False,
+                            num_threads=16)
+    parity.compare(out, ora, inp["uniforms"], inp["draft_len"])
+    assert out["accepted_len"].cpu().tolist()[3:7] == [-1, -1, -1, -1] and out["accepted_len"][7].item() == 0
