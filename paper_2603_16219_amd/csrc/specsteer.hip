@@ -903,6 +903,12 @@ hipError_t launch_all(LseArgs la, RecArgs ra, const Plan& pl, char* ws, hipStrea
     // the verdict's position-by-position log-probs are only complete in the one-pass schedule
     const int t1 = ra.draft_logprobs ? kmax : pl.t1;
     const bool two_pass = t1 < kmax;
+    hipError_t ev_err = hipSuccess;
+    auto mark = [&](int i) {  // stage boundary of the timed entry point
+        if (!ev) return;
+        const hipError_t e = hipEventRecord(ev[i], stream);
+        if (e != hipSuccess && ev_err == hipSuccess) ev_err = e;
+    };
     if (t1 != pl.t1) {  // one pass although the plan was made for two
         la.NS = pl.NSf;
         la.slice_vecs = pl.slice_vecsf;
@@ -921,29 +927,30 @@ hipError_t launch_all(LseArgs la, RecArgs ra, const Plan& pl, char* ws, hipStrea
     ra.NC = chunks_per_row(V, VEC);
     const size_t smem = (size_t)2 * kmax * sizeof(double) + (size_t)ra.NC * sizeof(Partial);
 
-    if (ev) hipEventRecord(ev[0], stream);
+    mark(0);
     if (kmax > 0)
         launch_row_pass<DT, VEC, VECFAST>(la, RowWindow{ragged ? ra.draft_len : nullptr, nullptr, kmax, 0, t1},
                                           ragged ? 0 : t1, off1, partial1, (long)B * t1, stream);
-    if (ev) hipEventRecord(ev[1], stream);
+    mark(1);
     if (two_pass)
         hipLaunchKernelGGL((verdict_kernel<DT>), dim3((unsigned)B), dim3(kRecThreads), (size_t)2 * kmax * sizeof(double),
                            stream, ra, alive, flagged, first_rej);
-    if (ev) hipEventRecord(ev[2], stream);
+    mark(2);
     if (two_pass) {
         la.NS = pl.NS2;
         la.slice_vecs = pl.slice_vecs2;
         launch_row_pass<DT, VEC, VECFAST>(la, RowWindow{ra.draft_len, alive, kmax, t1, kmax}, 0, off2, partial2,
                                           (long)B * (kmax - t1), stream);
     }
-    if (ev) hipEventRecord(ev[3], stream);
+    mark(3);
     // accept + recover: LDS holds the per-position log-probs and one mass per recovery chunk
     if (ra.greedy)
         hipLaunchKernelGGL((accept_recover_kernel<DT, VEC, true>), dim3((unsigned)B), dim3(kRecThreads), smem, stream, ra);
     else
         hipLaunchKernelGGL((accept_recover_kernel<DT, VEC, false>), dim3((unsigned)B), dim3(kRecThreads), smem, stream, ra);
-    if (ev) hipEventRecord(ev[4], stream);
-    return hipGetLastError();
+    mark(4);
+    const hipError_t launch_err = hipGetLastError();
+    return launch_err != hipSuccess ? launch_err : ev_err;
 }
 
 ss_status verify_block_impl(const void* G, const void* S_ctx, const void* S_noctx, const int32_t* draft,
@@ -1050,7 +1057,7 @@ ss_status specsteer_verify_block_timed(const void* G, const void* S_ctx, const v
                 if (hipEventElapsedTime(&stage_ms[i], ev[i], ev[i + 1]) != hipSuccess) st = SS_ERR_DEVICE;
         }
     }
-    for (int i = 0; i < made; ++i) hipEventDestroy(ev[i]);
+    for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
     return st;
 }
 

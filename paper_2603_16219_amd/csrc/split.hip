@@ -34,11 +34,6 @@ constexpr int kTopWaves = kTopThreads / kWave;
 constexpr int kTopUnroll = 2;  // vectors per tensor in flight per lane
 constexpr int kEdgeThreads = 256;
 
-struct Entry {
-    double v;
-    int idx;
-};
-
 // total order of the payload: larger value first, then smaller token id
 __device__ __forceinline__ bool beats(double av, int ai, double bv, int bi) {
     return av > bv || (av == bv && ai < bi);

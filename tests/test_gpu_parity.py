@@ -456,3 +456,49 @@ def test_two_pass_schedule_flags_bad_sequences_like_one_pass(binding, oracle):
                             num_threads=16)
     parity.compare(out, ora, inp["uniforms"], inp["draft_len"])
     assert out["accepted_len"].cpu().tolist()[3:7] == [-1, -1, -1, -1] and out["accepted_len"][7].item() == 0
+
+
+# ------------------------------------------------------------------ limits of the interface
+
+def test_batch_beyond_the_in_kernel_row_list(binding, oracle):
+    """More than 8192 sequences: the row list no longer fits LDS and is built by its own kernel."""
+    w = W.scaled(W.WORKLOADS["c4"], batch=9000, vocab=96, k_max=3, name="bigbatch")
+    inp = W.generate(w, "cuda", seq_chunk=512)
+    inp["draft_len"] = torch.randint(0, 4, (9000,), generator=torch.Generator("cuda").manual_seed(1), device="cuda",
+                                     dtype=torch.int32)
+    run_both(binding, oracle, w, inp)
+
+
+def test_big_batch_two_pass_with_global_row_lists(binding, oracle):
+    w = W.scaled(W.WORKLOADS["c4"], batch=9000, vocab=8192, k_max=4, name="bigbatch-twopass")
+    inp = W.generate(w, "cuda", seq_chunk=256)
+    p = binding.make_params(w.batch, w.k_max, w.vocab, inp["G"].dtype, lam=w.lam, beta=w.beta, temperature=w.temperature)
+    assert binding.first_window(p) == 1
+    out = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], lam=w.lam,
+                               beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"])
+    one = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], lam=w.lam,
+                               beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"], full_rows=True)
+    for k in ("accepted_len", "next_token", "next_token_logprob"):
+        assert torch.equal(out[k], one[k]), k
+    seqs = torch.arange(0, 9000, 9, device="cuda")
+    ora = parity.oracle_run(oracle, inp, lam=w.lam, beta=w.beta, temperature=w.temperature, seqs=seqs,
+                            want_recovery_logprobs=False, num_threads=16)
+    parity.compare(out, ora, inp["uniforms"], inp["draft_len"], seqs=seqs)
+
+
+def test_longest_draft_block(binding, oracle):
+    w = W.scaled(W.WORKLOADS["c2"], batch=2, vocab=200, k_max=1024, name="kmax1024")
+    inp = W.generate(w, "cuda")
+    inp["uniforms"][:, :1024] *= 0.001  # accept almost everything: the first rejection is far down the block
+    out, ora, rep = run_both(binding, oracle, w, inp)
+    assert rep["mean_accepted_len"] > 100
+
+
+@pytest.mark.parametrize("dtype,shift", [("bf16", 0), ("f32", 0), ("bf16", 1)])
+def test_largest_vocabulary(binding, oracle, dtype, shift):
+    """V = 2^20, the interface's maximum; shift = 1 moves the rows off 16-byte alignment (element-wise path)."""
+    import dataclasses
+    V = (1 << 20) - shift
+    w = dataclasses.replace(W.scaled(W.WORKLOADS["c2"], batch=2, vocab=V, k_max=2, name=f"vmax-{dtype}-{shift}"), dtype=dtype)
+    inp = W.generate(w, "cuda", seq_chunk=1)
+    run_both(binding, oracle, w, inp)
