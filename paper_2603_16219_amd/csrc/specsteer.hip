@@ -23,6 +23,9 @@
 //                  in LDS.  A double-precision scan over the chunk masses locates the
 //                  chunk holding u*Z; only that chunk is read again to pick the token.
 //                  The full log-prob row is a second sweep, taken only on request.
+//                  Batches of at most 128 sequences share each recovery row between
+//                  several workgroups; the one that delivers its chunk masses last
+//                  draws the token (see accept_recover_kernel).
 //
 // Precision: logits are widened exactly; sums of exponentials are accumulated in
 // fp32 (one rounding per term, pairwise across lanes), every per-row scalar
@@ -235,6 +238,8 @@ struct LseArgs {
     int slice_vecs;            // vectors (of the fast path's width) per slice
     int list_in_lds;           // build the row list in LDS (else row_off was filled by prep_rows)
     float c_hi;                // fl32(log2(e)/T)
+    uint32_t* zero_ptr;        // arrival counters of a split recovery: workgroup 0 clears zero_n of them
+    int zero_n;
 };
 
 // Work item = (row, tensor, slice), flattened so that consecutive items are consecutive slices
@@ -256,6 +261,8 @@ __global__ __launch_bounds__(kLseThreads) void row_lse_kernel(const LseArgs a) {
     }
     if (blockIdx.x == 0 && ragged && a.list_in_lds)
         for (int i = threadIdx.x; i <= a.B; i += kLseThreads) a.row_off[i] = lds_off[i];
+    if (blockIdx.x == 0)
+        for (int i = threadIdx.x; i < a.zero_n; i += kLseThreads) a.zero_ptr[i] = 0u;
     const int R = ragged ? off[a.B] : a.B * a.uniform_rows;
     const long items = (long)R * 2 * a.NS;
     // a slice is slice_vecs vectors of the fast width; the element-wise path covers the same logits
@@ -353,6 +360,11 @@ struct RecArgs {
     double ln_lambda;
     double rho;      // (c - fl32(c)) / fl32(c): first-order repair of the row pass's rounded scale
     int greedy;      // SS_FLAG_GREEDY
+    // Split recovery (small batches): `parts` workgroups share the recovery row of one sequence.
+    int parts;
+    Partial* chunk_tab;   // [B][NC] chunk masses, filled by the parts
+    Best* part_best;      // [B][parts] greedy candidates of the parts
+    uint32_t* arrive;     // [B] parts that have delivered; cleared by the first row pass
 };
 
 // log2 of sum_v 2^(h_v * c) for one row from its slice partials, by one wave: lane k holds
@@ -658,6 +670,19 @@ __global__ __launch_bounds__(kRecThreads) void verdict_kernel(const RecArgs a, i
     }
 }
 
+// Best candidate of the wave, left in every lane: larger value, then lower index.
+__device__ __forceinline__ void wave_best(Best& best) {
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const double ov = __shfl_xor(best.v, d, kWave);
+        const long oi = __shfl_xor(best.idx, d, kWave);
+        if (ov > best.v || (ov == best.v && oi < best.idx)) {
+            best.v = ov;
+            best.idx = oi;
+        }
+    }
+}
+
 // One workgroup (16 waves) per sequence, everything after the row pass in one launch:
 //   2a  every (position, tensor) pair gets a wave: merge its slice partials, gather the draft
 //       token's logit, leave log P(y_t) in LDS            (two memory round trips in all)
@@ -666,15 +691,24 @@ __global__ __launch_bounds__(kRecThreads) void verdict_kernel(const RecArgs a, i
 //       mass per 2048-logit chunk into LDS
 //   4   wave 0 draws the token; optionally all waves sweep the rows again to write log-probs
 // Only workgroup barriers separate the steps; nothing crosses workgroups.
-template <int DT, int VEC, bool GREEDY>
+//
+// SPLIT (small batches, where one workgroup per sequence leaves most of the chip idle): a.parts
+// workgroups share a sequence.  Each repeats steps 2a-2b (cheap), takes every a.parts-th group of
+// 16 chunks in step 3 and delivers its chunk masses to a table in global memory; the part that
+// arrives last (an atomic counter per sequence, no workgroup ever waits for another) runs step 4
+// from the complete table.  The deliveries are made, fenced and counted by one wave, and the
+// last part's reading wave fences before it reads.
+template <int DT, int VEC, bool GREEDY, bool SPLIT>
 __global__ __launch_bounds__(kRecThreads) void accept_recover_kernel(const RecArgs a) {
     extern __shared__ double smem_d[];
-    __shared__ int sh_n, sh_bad;
+    __shared__ int sh_n, sh_bad, sh_last;
     __shared__ double sh_log2Z;
     __shared__ double sh_best_v[kRecThreads / kWave];
     __shared__ long sh_best_i[kRecThreads / kWave];
 
-    const int b = blockIdx.x;
+    const int S = SPLIT ? a.parts : 1;
+    const int b = SPLIT ? (int)blockIdx.x / S : (int)blockIdx.x;
+    const int part = SPLIT ? (int)blockIdx.x - b * S : 0;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     constexpr int NW = kRecThreads / kWave;
     const int kmax = a.kmax, V = a.V;
@@ -695,13 +729,13 @@ __global__ __launch_bounds__(kRecThreads) void accept_recover_kernel(const RecAr
     __syncthreads();
     if (!settled) ratio_test_block<DT>(a, b, Kt, lp, &sh_n, &sh_bad);
     const bool bad = sh_bad != 0;
-    if (a.draft_logprobs) {  // valid positions from LDS, padded slots 0, a flagged sequence NaN throughout
+    if (a.draft_logprobs && part == 0) {  // valid positions from LDS, padded slots 0, a flagged sequence NaN throughout
         const float nanv = __int_as_float(0x7FC00000);
         for (int i = tid; i < kmax * 2; i += kRecThreads)
             a.draft_logprobs[(long)b * kmax * 2 + i] = bad ? nanv : (i < 2 * Kt ? (float)lp[i] : 0.f);
     }
     if (bad) {
-        if (tid == 0) {
+        if (tid == 0 && part == 0) {
             a.accepted_len[b] = -1;
             a.next_token[b] = -1;
             if (a.next_token_logprob) a.next_token_logprob[b] = __int_as_float(0x7FC00000);
@@ -720,20 +754,12 @@ __global__ __launch_bounds__(kRecThreads) void accept_recover_kernel(const RecAr
     const int tailc = V - (int)(nvec * VEC);
     const long nch = (nvec + kWave * kChunkSteps - 1) / (kWave * kChunkSteps);
     Best best{-__builtin_huge_val(), 0x7FFFFFFFFFFFFFFFl};
-    for (int c = wave; c < a.NC; c += NW) {
+    for (int c = part * NW + wave; c < a.NC; c += NW * S) {
         const Partial p = chunk_mass<DT, VEC, GREEDY>(g, sp, sm, nvec, tailc, nch, c, lane, a.c, a.bc, a.beta, best);
         if (lane == 0) tab[c] = p;
     }
-    if (GREEDY) {  // best of the wave: larger value, then lower index
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            const double ov = __shfl_xor(best.v, d, kWave);
-            const long oi = __shfl_xor(best.idx, d, kWave);
-            if (ov > best.v || (ov == best.v && oi < best.idx)) {
-                best.v = ov;
-                best.idx = oi;
-            }
-        }
+    if (GREEDY) {
+        wave_best(best);
         if (lane == 0) {
             sh_best_v[wave] = best.v;
             sh_best_i[wave] = best.idx;
@@ -741,20 +767,44 @@ __global__ __launch_bounds__(kRecThreads) void accept_recover_kernel(const RecAr
     }
     __syncthreads();
 
+    if (SPLIT) {  // deliver this part; only the last part to arrive goes on
+        if (wave == 0) {
+            Partial* gtab = a.chunk_tab + (long)b * a.NC;
+            for (int c = lane; c < a.NC; c += kWave)
+                if ((c / NW) % S == part) gtab[c] = tab[c];
+            if (GREEDY) {
+                best.v = lane < NW ? sh_best_v[lane] : -__builtin_huge_val();
+                best.idx = lane < NW ? sh_best_i[lane] : 0x7FFFFFFFFFFFFFFFl;
+                wave_best(best);
+                if (lane == 0) a.part_best[(long)b * S + part] = best;
+            }
+            __threadfence();  // this wave's deliveries are visible device-wide before it is counted
+            unsigned prev = 0;
+            if (lane == 0) prev = __hip_atomic_fetch_add(a.arrive + b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (lane == 0) sh_last = (prev == (unsigned)(S - 1)) ? 1 : 0;
+        }
+        __syncthreads();
+        if (!sh_last) return;
+        if (wave == 0) {
+            __threadfence();  // the other parts' deliveries, not a stale cached copy
+            const Partial* gtab = a.chunk_tab + (long)b * a.NC;
+            for (int c = lane; c < a.NC; c += kWave) tab[c] = gtab[c];
+            if (GREEDY && lane < S) {
+                const Best o = a.part_best[(long)b * S + lane];
+                sh_best_v[lane] = o.v;
+                sh_best_i[lane] = o.idx;
+            }
+        }
+        __syncthreads();
+    }
+
     // ---- 4
     if (wave == 0) {
         if (GREEDY) {
-            best.v = lane < NW ? sh_best_v[lane] : -__builtin_huge_val();
-            best.idx = lane < NW ? sh_best_i[lane] : 0x7FFFFFFFFFFFFFFFl;
-#pragma unroll
-            for (int d = 1; d < NW; d <<= 1) {
-                const double ov = __shfl_xor(best.v, d, kWave);
-                const long oi = __shfl_xor(best.idx, d, kWave);
-                if (ov > best.v || (ov == best.v && oi < best.idx)) {
-                    best.v = ov;
-                    best.idx = oi;
-                }
-            }
+            const int NB = SPLIT ? S : NW;
+            best.v = lane < NB ? sh_best_v[lane] : -__builtin_huge_val();
+            best.idx = lane < NB ? sh_best_i[lane] : 0x7FFFFFFFFFFFFFFFl;
+            wave_best(best);
         }
         const double log2Z = sample_wave<DT, VEC, GREEDY>(a, b, n, lane, tab, g, sp, sm, nvec, tailc, nch, best);
         if (lane == 0) sh_log2Z = log2Z;
@@ -779,6 +829,10 @@ __global__ __launch_bounds__(kRecThreads) void accept_recover_kernel(const RecAr
     }
 }
 
+__global__ void zero_u32_kernel(uint32_t* p, int n) {
+    for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0u;
+}
+
 // ------------------------------------------------------------------ host side
 
 struct Plan {
@@ -788,8 +842,25 @@ struct Plan {
     int NSf, slice_vecsf;  // one pass over all k_max positions (taken when draft_logprobs is requested)
     int t1;          // positions in the first row pass; == k_max when the block is verified in one pass
     size_t off_list2, off_alive, off_flagged, off_firstrej, off_partial;
+    size_t off_arrive, off_part_best, off_chunk_tab;  // split recovery; only present for small batches
     size_t bytes;
 };
+
+// Small batches split each sequence's recovery row over several workgroups so that the sweep is
+// not tied to the rate of one compute unit per sequence.  The chip has 256 compute units; a part
+// is worth having only if it gets a full round of 16 chunks.
+constexpr int kSplitMaxBatch = 128;
+constexpr int kSplitMaxParts = 16;  // one LDS slot per part in the greedy merge
+constexpr int kChipCus = 256;
+
+int recovery_parts(int B, int NC) {
+    if (B < 1 || B > kSplitMaxBatch) return 1;
+    const int by_chunks = (NC + (kRecThreads / kWave) - 1) / (kRecThreads / kWave);
+    int parts = kChipCus / B;
+    if (parts > by_chunks) parts = by_chunks;
+    if (parts > kSplitMaxParts) parts = kSplitMaxParts;
+    return parts < 1 ? 1 : parts;
+}
 
 // Two row passes pay off when the batch is large enough to be bandwidth-bound and long enough for
 // a first rejection to cut rows: the first quarter of the positions is scored for everyone, the
@@ -861,6 +932,14 @@ Plan make_plan(const ss_params* p) {
     size_t ns_max = (size_t)(pl.NS > pl.NS2 ? pl.NS : pl.NS2);
     if ((size_t)pl.NSf > ns_max) ns_max = (size_t)pl.NSf;
     o += align_up(((size_t)p->batch * p->k_max * 2 + 1) * ns_max * sizeof(Partial), 256);
+    pl.off_arrive = pl.off_part_best = pl.off_chunk_tab = o;
+    if (p->batch >= 1 && p->batch <= kSplitMaxBatch) {
+        pl.off_arrive = o;     o += align_up(B * sizeof(uint32_t), 256);
+        pl.off_part_best = o;  o += align_up(B * kSplitMaxParts * sizeof(Best), 256);
+        // sized for whichever path has more chunks (normally the element-wise one, whose chunks are smaller)
+        const int nc1 = chunks_per_row(p->vocab, 1), ncf = chunks_per_row(p->vocab, pl.vecfast);
+        pl.off_chunk_tab = o;  o += align_up(B * (size_t)(nc1 > ncf ? nc1 : ncf) * sizeof(Partial), 256);
+    }
     pl.bytes = o;
     return pl;
 }
@@ -925,9 +1004,18 @@ hipError_t launch_all(LseArgs la, RecArgs ra, const Plan& pl, char* ws, hipStrea
     ra.flagged = two_pass ? flagged : nullptr;
     ra.first_rej = two_pass ? first_rej : nullptr;
     ra.NC = chunks_per_row(V, VEC);
+    ra.parts = recovery_parts(B, ra.NC);
+    ra.arrive = reinterpret_cast<uint32_t*>(ws + pl.off_arrive);
+    ra.part_best = reinterpret_cast<Best*>(ws + pl.off_part_best);
+    ra.chunk_tab = reinterpret_cast<Partial*>(ws + pl.off_chunk_tab);
+    const bool split = ra.parts > 1;
+    la.zero_ptr = ra.arrive;
+    la.zero_n = split ? B : 0;
     const size_t smem = (size_t)2 * kmax * sizeof(double) + (size_t)ra.NC * sizeof(Partial);
 
     mark(0);
+    if (kmax == 0 && split)  // no row pass to clear the arrival counters
+        hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(kSplitMaxBatch), 0, stream, ra.arrive, B);
     if (kmax > 0)
         launch_row_pass<DT, VEC, VECFAST>(la, RowWindow{ragged ? ra.draft_len : nullptr, nullptr, kmax, 0, t1},
                                           ragged ? 0 : t1, off1, partial1, (long)B * t1, stream);
@@ -939,15 +1027,24 @@ hipError_t launch_all(LseArgs la, RecArgs ra, const Plan& pl, char* ws, hipStrea
     if (two_pass) {
         la.NS = pl.NS2;
         la.slice_vecs = pl.slice_vecs2;
+        la.zero_n = 0;
         launch_row_pass<DT, VEC, VECFAST>(la, RowWindow{ra.draft_len, alive, kmax, t1, kmax}, 0, off2, partial2,
                                           (long)B * (kmax - t1), stream);
     }
     mark(3);
     // accept + recover: LDS holds the per-position log-probs and one mass per recovery chunk
-    if (ra.greedy)
-        hipLaunchKernelGGL((accept_recover_kernel<DT, VEC, true>), dim3((unsigned)B), dim3(kRecThreads), smem, stream, ra);
-    else
-        hipLaunchKernelGGL((accept_recover_kernel<DT, VEC, false>), dim3((unsigned)B), dim3(kRecThreads), smem, stream, ra);
+    const dim3 rec_grid((unsigned)(B * ra.parts));
+    if (split) {
+        if (ra.greedy)
+            hipLaunchKernelGGL((accept_recover_kernel<DT, VEC, true, true>), rec_grid, dim3(kRecThreads), smem, stream, ra);
+        else
+            hipLaunchKernelGGL((accept_recover_kernel<DT, VEC, false, true>), rec_grid, dim3(kRecThreads), smem, stream, ra);
+    } else {
+        if (ra.greedy)
+            hipLaunchKernelGGL((accept_recover_kernel<DT, VEC, true, false>), rec_grid, dim3(kRecThreads), smem, stream, ra);
+        else
+            hipLaunchKernelGGL((accept_recover_kernel<DT, VEC, false, false>), rec_grid, dim3(kRecThreads), smem, stream, ra);
+    }
     mark(4);
     const hipError_t launch_err = hipGetLastError();
     return launch_err != hipSuccess ? launch_err : ev_err;
@@ -993,6 +1090,7 @@ ss_status verify_block_impl(const void* G, const void* S_ctx, const void* S_noct
     la.win = RowWindow{nullptr, nullptr, params->k_max, 0, params->k_max};
     la.sb = sb; la.st = st; la.B = params->batch; la.kmax = params->k_max; la.V = params->vocab;
     la.NS = pl.NS; la.slice_vecs = pl.slice_vecs; la.list_in_lds = 0; la.c_hi = c_hi;
+    la.zero_ptr = nullptr; la.zero_n = 0;
 
     RecArgs ra;
     const bool steer = params->beta != 0.f;
@@ -1005,6 +1103,7 @@ ss_status verify_block_impl(const void* G, const void* S_ctx, const void* S_noct
     ra.rho = (c - (double)c_hi) / (double)c_hi;
     ra.beta = (double)params->beta;
     ra.greedy = (params->flags & SS_FLAG_GREEDY) ? 1 : 0;
+    ra.parts = 1; ra.chunk_tab = nullptr; ra.part_best = nullptr; ra.arrive = nullptr;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t err;

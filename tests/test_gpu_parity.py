@@ -502,3 +502,62 @@ def test_largest_vocabulary(binding, oracle, dtype, shift):
     w = dataclasses.replace(W.scaled(W.WORKLOADS["c2"], batch=2, vocab=V, k_max=2, name=f"vmax-{dtype}-{shift}"), dtype=dtype)
     inp = W.generate(w, "cuda", seq_chunk=1)
     run_both(binding, oracle, w, inp)
+
+
+# ------------------------------------------------------------------ small batches: recovery row shared by several workgroups
+
+@pytest.mark.parametrize("name,batch,vocab,dtype", [
+    ("c2", 1, 151936, "bf16"),    # the on-device case: one sequence, 5 parts
+    ("c2", 17, 151936, "bf16"),   # 256 // 17 = 15 parts wanted, 5 available
+    ("c4", 128, 32776, "bf16"),   # 2 parts, the second holds a single chunk
+    ("c4", 100, 70000, "bf16"),   # 2 parts of 3 wanted by the chunks
+    ("c1", 1, 32000, "f32"),
+    ("c5", 33, 65544, "f32"),     # 7 parts
+    ("c3", 16, 151937, "bf16"),   # odd vocabulary: element-wise path, 16 parts
+])
+def test_split_recovery_shapes(binding, oracle, name, batch, vocab, dtype):
+    import dataclasses
+    w = dataclasses.replace(W.scaled(W.WORKLOADS[name], batch=batch, vocab=vocab, name=f"split-{name}-{batch}"),
+                            dtype=dtype)
+    inp = W.generate(w, "cuda")
+    run_both(binding, oracle, w, inp)
+    out = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], lam=w.lam,
+                               beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"], greedy=True)
+    ora = parity.oracle_run(oracle, inp, lam=w.lam, beta=w.beta, temperature=w.temperature, greedy=True,
+                            want_recovery_logprobs=False, num_threads=16)
+    rep = parity.compare(out, ora, inp["uniforms"], inp["draft_len"])
+    assert rep["near_threshold_samples"] == 0
+
+
+def test_split_recovery_reuses_one_workspace(binding, oracle):
+    """Back-to-back calls on one workspace, the arrival counters of the parts start from zero
+    every time; sampled, greedy and draft-free calls interleaved, with flagged sequences."""
+    w = W.scaled(W.WORKLOADS["c4"], batch=12, vocab=128256, name="split-ws")
+    p = binding.make_params(w.batch, w.k_max, w.vocab, torch.bfloat16, lam=w.lam, beta=w.beta, temperature=w.temperature)
+    ws = torch.empty(binding.workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xAB)
+    for rnd in range(4):
+        inp = W.generate(w, "cuda", seed_shift=rnd)
+        greedy = rnd == 2
+        if rnd == 1:
+            inp["draft_len"][3] = w.k_max + 1
+            inp["draft"][7, 0] = w.vocab
+        out = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], lam=w.lam,
+                                   beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"],
+                                   want_recovery_logprobs=True, greedy=greedy, workspace=ws)
+        ora = parity.oracle_run(oracle, inp, lam=w.lam, beta=w.beta, temperature=w.temperature, greedy=greedy,
+                                num_threads=16)
+        rep = parity.compare(out, ora, inp["uniforms"], inp["draft_len"])
+        print(f"\n[split-ws {rnd}] {rep}", flush=True)
+        if rnd == 1:
+            assert out["accepted_len"][3].item() == -1 and out["accepted_len"][7].item() == -1
+    # rows without drafts (k_max = 0) have no row pass in front of the recovery
+    w0 = W.scaled(W.WORKLOADS["c2"], batch=5, vocab=100000, k_max=0, name="split-k0")
+    p0 = binding.make_params(w0.batch, 0, w0.vocab, torch.bfloat16, lam=w0.lam, beta=w0.beta, temperature=w0.temperature)
+    ws0 = torch.full((binding.workspace_bytes(p0),), 0xCD, dtype=torch.uint8, device="cuda")
+    for rnd in range(2):
+        inp = W.generate(w0, "cuda", seed_shift=rnd)
+        out = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], lam=w0.lam,
+                                   beta=w0.beta, temperature=w0.temperature, want_recovery_logprobs=True, workspace=ws0)
+        ora = parity.oracle_run(oracle, inp, lam=w0.lam, beta=w0.beta, temperature=w0.temperature, num_threads=16)
+        parity.compare(out, ora, inp["uniforms"], inp["draft_len"])
