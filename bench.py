@@ -261,22 +261,28 @@ def main() -> int:
 
         oracle.build()
         s = sets[0]
-        # bounded sample: whole sequences, chosen so the oracle does roughly 10-30 s of CPU work
+        # bounded sample: whole sequences, at most ~6e8 exponentials per pass (the whole batch for c1-c4)
         exps_per_seq = (2.0 * positions[0] / B + 1.5) * V
         nseq = int(max(1, min(B, 6e8 // max(exps_per_seq, 1))))
         threads = min(oracle.max_threads(), int(os.environ.get("OMP_NUM_THREADS", "16")), nseq)
         seqs = torch.arange(nseq, device=dev)
         host = {k: (None if v is None else v[:nseq].cpu()) for k, v in s.items()}
-        t1 = time.perf_counter()
-        ora = oracle.verify_block(host["G"], host["S_ctx"], host["S_noctx"], host["draft"], host["uniforms"],
-                                  lam=w.lam, beta=w.beta, temperature=w.temperature, draft_len=host["draft_len"],
-                                  want_recovery_logprobs=False, num_threads=threads, greedy=args.mode == "greedy")
-        cpu_s = time.perf_counter() - t1
+        # the oracle stops at the first rejection as Algorithm 1 does, so one pass is short: repeat it
+        # (same inputs) until about a second of wall time has gone by and report the median pass
+        walls = []
+        while len(walls) < 9 and (sum(walls) < 1.0 or len(walls) < 3):
+            t1 = time.perf_counter()
+            ora = oracle.verify_block(host["G"], host["S_ctx"], host["S_noctx"], host["draft"], host["uniforms"],
+                                      lam=w.lam, beta=w.beta, temperature=w.temperature, draft_len=host["draft_len"],
+                                      want_recovery_logprobs=False, num_threads=threads, greedy=args.mode == "greedy")
+            walls.append(time.perf_counter() - t1)
+        cpu_s = sorted(walls)[len(walls) // 2]
         cpu_pos = int(host["draft_len"].sum().item()) if host["draft_len"] is not None else nseq * kmax
         out["cpu_baseline"] = {
             "value": cpu_pos / cpu_s, "unit": "positions/s", "cores": threads, "kind": "oracle",
             "sample": f"first {nseq} of {B} sequences of {w.name} ({cpu_pos} positions), float64 oracle, "
-                      f"{threads} OpenMP threads over sequences, {cpu_s:.2f} s wall",
+                      f"{threads} OpenMP threads over sequences, median of {len(walls)} passes of {cpu_s:.3f} s wall "
+                      f"({sum(walls) * threads:.0f} CPU-seconds in all)",
         }
         # parity of the same step against the oracle, reported beside the timing: the step as timed, plus a
         # second call that also asks for the per-position log-probs (which takes the one-pass schedule)

@@ -360,6 +360,7 @@ struct RecArgs {
     double ln_lambda;
     double rho;      // (c - fl32(c)) / fl32(c): first-order repair of the row pass's rounded scale
     int greedy;      // SS_FLAG_GREEDY
+    int plain;       // beta == 0: no steering term, the specialist rows are not read by the recovery sweep
     // Split recovery (small batches): `parts` workgroups share the recovery row of one sequence.
     int parts;
     Partial* chunk_tab;   // [B][NC] chunk masses, filled by the parts
@@ -380,11 +381,30 @@ __device__ __forceinline__ double combine_partials_wave(const Partial* p, int NS
     return (double)m.E * (1.0 + rho) + log2((double)m.s);  // E*rho: see acc_add_f32
 }
 
+// PLAIN (beta == 0): the recovery distribution is Softmax(h_LLM / T); the two specialist rows are
+// neither loaded nor unpacked, their logits read as 0 so that the steering term is an exact zero.
+template <int DT, int VEC, bool PLAIN>
+__device__ __forceinline__ void unpack_steer(const typename RawT<DT, VEC>::type& rp, const typename RawT<DT, VEC>::type& rm,
+                                             float (&hp)[VEC], float (&hm)[VEC]) {
+    if (PLAIN) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) hp[i] = hm[i] = 0.f;
+    } else {
+        unpack(rp, hp);
+        unpack(rm, hm);
+    }
+}
+
+template <int DT, bool PLAIN>
+__device__ __forceinline__ float ld_steer(const void* row, long e) {
+    return PLAIN ? 0.f : ld_elem<DT>(row, e);
+}
+
 // Probability terms 2^(y - E*) of the logits one lane owns in recovery chunk c, laid out so that
 // a lane's logits are consecutive in the vocabulary: lane l holds vectors 4l..4l+3 of the chunk.
 // The pseudo-chunk c == nch holds the < VEC logits past the last full vector, one per lane.
 // cnt[j] says how many entries of p[j] are valid; first[j] is the vocabulary index of p[j][0].
-template <int DT, int VEC>
+template <int DT, int VEC, bool PLAIN>
 __device__ __forceinline__ void chunk_lane_terms(const void* g, const void* sp, const void* sm, long nvec, int tailc,
                                                  long nch, long c, int lane, double cc, double bc, double dE,
                                                  float (&p)[kChunkSteps][VEC], long (&first)[kChunkSteps],
@@ -397,8 +417,10 @@ __device__ __forceinline__ void chunk_lane_terms(const void* g, const void* sp, 
         first[j] = v * VEC;
         if (c < nch && v < nvec) {
             rg[j] = ld_raw<DT, VEC>(g, v);
-            rp[j] = ld_raw<DT, VEC>(sp, v);
-            rm[j] = ld_raw<DT, VEC>(sm, v);
+            if (!PLAIN) {
+                rp[j] = ld_raw<DT, VEC>(sp, v);
+                rm[j] = ld_raw<DT, VEC>(sm, v);
+            }
             cnt[j] = VEC;
         }
     }
@@ -409,8 +431,7 @@ __device__ __forceinline__ void chunk_lane_terms(const void* g, const void* sp, 
         if (cnt[j]) {
             float hg[VEC], hp[VEC], hm[VEC];
             unpack(rg[j], hg);
-            unpack(rp[j], hp);
-            unpack(rm[j], hm);
+            unpack_steer<DT, VEC, PLAIN>(rp[j], rm[j], hp, hm);
 #pragma unroll
             for (int i = 0; i < VEC; ++i)
                 p[j][i] = __builtin_amdgcn_exp2f((float)(rec_y(hg[i], hp[i], hm[i], cc, bc) - dE));
@@ -419,13 +440,13 @@ __device__ __forceinline__ void chunk_lane_terms(const void* g, const void* sp, 
     if (c >= nch && lane < tailc) {
         first[0] = nvec * VEC + lane;
         cnt[0] = 1;
-        p[0][0] = __builtin_amdgcn_exp2f(
-            (float)(rec_y(ld_elem<DT>(g, first[0]), ld_elem<DT>(sp, first[0]), ld_elem<DT>(sm, first[0]), cc, bc) - dE));
+        p[0][0] = __builtin_amdgcn_exp2f((float)(rec_y(ld_elem<DT>(g, first[0]), ld_steer<DT, PLAIN>(sp, first[0]),
+                                                       ld_steer<DT, PLAIN>(sm, first[0]), cc, bc) - dE));
     }
 }
 
 // (E, s) mass of recovery chunk c, by one wave: sum over the chunk of 2^(y - E).
-template <int DT, int VEC, bool GREEDY>
+template <int DT, int VEC, bool GREEDY, bool PLAIN>
 __device__ __forceinline__ Partial chunk_mass(const void* g, const void* sp, const void* sm, long nvec, int tailc,
                                               long nch, long c, int lane, double cc, double bc, double beta,
                                               Best& best) {
@@ -439,8 +460,10 @@ __device__ __forceinline__ Partial chunk_mass(const void* g, const void* sp, con
             const long v = vbase + (long)j * kWave;
             if (v < nvec) {
                 rg[j] = ld_raw<DT, VEC>(g, v);
-                rp[j] = ld_raw<DT, VEC>(sp, v);
-                rm[j] = ld_raw<DT, VEC>(sm, v);
+                if (!PLAIN) {
+                    rp[j] = ld_raw<DT, VEC>(sp, v);
+                    rm[j] = ld_raw<DT, VEC>(sm, v);
+                }
             }
         }
 #pragma unroll
@@ -449,14 +472,13 @@ __device__ __forceinline__ Partial chunk_mass(const void* g, const void* sp, con
             if (v < nvec) {
                 float hg[VEC], hp[VEC], hm[VEC];
                 unpack(rg[j], hg);
-                unpack(rp[j], hp);
-                unpack(rm[j], hm);
+                unpack_steer<DT, VEC, PLAIN>(rp[j], rm[j], hp, hm);
                 acc_add_rec<DT, VEC, GREEDY>(acc, hg, hp, hm, cc, bc, cf, bcf, beta, v * VEC, best);
             }
         }
     } else if (lane < tailc) {
         const long e = nvec * VEC + lane;
-        const float hg[1] = {ld_elem<DT>(g, e)}, hp[1] = {ld_elem<DT>(sp, e)}, hm[1] = {ld_elem<DT>(sm, e)};
+        const float hg[1] = {ld_elem<DT>(g, e)}, hp[1] = {ld_steer<DT, PLAIN>(sp, e)}, hm[1] = {ld_steer<DT, PLAIN>(sm, e)};
         acc_add_rec<DT, 1, GREEDY>(acc, hg, hp, hm, cc, bc, cf, bcf, beta, e, best);
     }
     return wave_combine(acc);
@@ -465,7 +487,7 @@ __device__ __forceinline__ Partial chunk_mass(const void* g, const void* sp, con
 // Inverse-CDF draw for one sequence by one wave, from the chunk masses `tab` (LDS) of its
 // recovery row: a double-precision scan over the masses finds the chunk holding u*Z, and only
 // that chunk is read again to pick the token.  Returns log2 Z; writes the per-sequence outputs.
-template <int DT, int VEC, bool GREEDY>
+template <int DT, int VEC, bool GREEDY, bool PLAIN>
 __device__ __forceinline__ double sample_wave(const RecArgs& a, int b, int n, int lane, const Partial* tab,
                                               const void* g, const void* sp, const void* sm, long nvec, int tailc,
                                               long nch, Best greedy_pick) {
@@ -525,7 +547,7 @@ __device__ __forceinline__ double sample_wave(const RecArgs& a, int b, int n, in
     float p[kChunkSteps][VEC];
     long first[kChunkSteps];
     int cnt[kChunkSteps];
-    chunk_lane_terms<DT, VEC>(g, sp, sm, nvec, tailc, nch, cstar, lane, a.c, a.bc, dE, p, first, cnt);
+    chunk_lane_terms<DT, VEC, PLAIN>(g, sp, sm, nvec, tailc, nch, cstar, lane, a.c, a.bc, dE, p, first, cnt);
     double ls = 0.0;
     long lastpos = -1;
 #pragma unroll
@@ -698,7 +720,7 @@ __device__ __forceinline__ void wave_best(Best& best) {
 // arrives last (an atomic counter per sequence, no workgroup ever waits for another) runs step 4
 // from the complete table.  The deliveries are made, fenced and counted by one wave, and the
 // last part's reading wave fences before it reads.
-template <int DT, int VEC, bool GREEDY, bool SPLIT>
+template <int DT, int VEC, bool GREEDY, bool SPLIT, bool PLAIN>
 __global__ __launch_bounds__(kRecThreads) void accept_recover_kernel(const RecArgs a) {
     extern __shared__ double smem_d[];
     __shared__ int sh_n, sh_bad, sh_last;
@@ -755,7 +777,7 @@ __global__ __launch_bounds__(kRecThreads) void accept_recover_kernel(const RecAr
     const long nch = (nvec + kWave * kChunkSteps - 1) / (kWave * kChunkSteps);
     Best best{-__builtin_huge_val(), 0x7FFFFFFFFFFFFFFFl};
     for (int c = part * NW + wave; c < a.NC; c += NW * S) {
-        const Partial p = chunk_mass<DT, VEC, GREEDY>(g, sp, sm, nvec, tailc, nch, c, lane, a.c, a.bc, a.beta, best);
+        const Partial p = chunk_mass<DT, VEC, GREEDY, PLAIN>(g, sp, sm, nvec, tailc, nch, c, lane, a.c, a.bc, a.beta, best);
         if (lane == 0) tab[c] = p;
     }
     if (GREEDY) {
@@ -806,7 +828,7 @@ __global__ __launch_bounds__(kRecThreads) void accept_recover_kernel(const RecAr
             best.idx = lane < NB ? sh_best_i[lane] : 0x7FFFFFFFFFFFFFFFl;
             wave_best(best);
         }
-        const double log2Z = sample_wave<DT, VEC, GREEDY>(a, b, n, lane, tab, g, sp, sm, nvec, tailc, nch, best);
+        const double log2Z = sample_wave<DT, VEC, GREEDY, PLAIN>(a, b, n, lane, tab, g, sp, sm, nvec, tailc, nch, best);
         if (lane == 0) sh_log2Z = log2Z;
     }
     if (a.recovery_logprobs) {
@@ -816,15 +838,20 @@ __global__ __launch_bounds__(kRecThreads) void accept_recover_kernel(const RecAr
         for (long v = tid; v < nvec; v += kRecThreads) {
             float hg[VEC], hp[VEC], hm[VEC];
             unpack(ld_raw<DT, VEC>(g, v), hg);
-            unpack(ld_raw<DT, VEC>(sp, v), hp);
-            unpack(ld_raw<DT, VEC>(sm, v), hm);
+            if (PLAIN) {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) hp[i] = hm[i] = 0.f;
+            } else {
+                unpack(ld_raw<DT, VEC>(sp, v), hp);
+                unpack(ld_raw<DT, VEC>(sm, v), hm);
+            }
 #pragma unroll
             for (int i = 0; i < VEC; ++i)
                 out[v * VEC + i] = (float)(kLn2 * (rec_y(hg[i], hp[i], hm[i], a.c, a.bc) - log2Z));
         }
         if (tid < tailc) {
             const long e = nvec * VEC + tid;
-            out[e] = (float)(kLn2 * (rec_y(ld_elem<DT>(g, e), ld_elem<DT>(sp, e), ld_elem<DT>(sm, e), a.c, a.bc) - log2Z));
+            out[e] = (float)(kLn2 * (rec_y(ld_elem<DT>(g, e), ld_steer<DT, PLAIN>(sp, e), ld_steer<DT, PLAIN>(sm, e), a.c, a.bc) - log2Z));
         }
     }
 }
@@ -1034,17 +1061,14 @@ hipError_t launch_all(LseArgs la, RecArgs ra, const Plan& pl, char* ws, hipStrea
     mark(3);
     // accept + recover: LDS holds the per-position log-probs and one mass per recovery chunk
     const dim3 rec_grid((unsigned)(B * ra.parts));
-    if (split) {
-        if (ra.greedy)
-            hipLaunchKernelGGL((accept_recover_kernel<DT, VEC, true, true>), rec_grid, dim3(kRecThreads), smem, stream, ra);
-        else
-            hipLaunchKernelGGL((accept_recover_kernel<DT, VEC, false, true>), rec_grid, dim3(kRecThreads), smem, stream, ra);
-    } else {
-        if (ra.greedy)
-            hipLaunchKernelGGL((accept_recover_kernel<DT, VEC, true, false>), rec_grid, dim3(kRecThreads), smem, stream, ra);
-        else
-            hipLaunchKernelGGL((accept_recover_kernel<DT, VEC, false, false>), rec_grid, dim3(kRecThreads), smem, stream, ra);
-    }
+    using RecKernel = void (*)(RecArgs);
+    static const RecKernel rec_kernels[8] = {  // index: greedy | split << 1 | plain << 2
+        accept_recover_kernel<DT, VEC, false, false, false>, accept_recover_kernel<DT, VEC, true, false, false>,
+        accept_recover_kernel<DT, VEC, false, true, false>,  accept_recover_kernel<DT, VEC, true, true, false>,
+        accept_recover_kernel<DT, VEC, false, false, true>,  accept_recover_kernel<DT, VEC, true, false, true>,
+        accept_recover_kernel<DT, VEC, false, true, true>,   accept_recover_kernel<DT, VEC, true, true, true>};
+    hipLaunchKernelGGL(rec_kernels[(ra.greedy ? 1 : 0) | (split ? 2 : 0) | (ra.plain ? 4 : 0)], rec_grid,
+                       dim3(kRecThreads), smem, stream, ra);
     mark(4);
     const hipError_t launch_err = hipGetLastError();
     return launch_err != hipSuccess ? launch_err : ev_err;
@@ -1103,6 +1127,7 @@ ss_status verify_block_impl(const void* G, const void* S_ctx, const void* S_noct
     ra.rho = (c - (double)c_hi) / (double)c_hi;
     ra.beta = (double)params->beta;
     ra.greedy = (params->flags & SS_FLAG_GREEDY) ? 1 : 0;
+    ra.plain = steer ? 0 : 1;
     ra.parts = 1; ra.chunk_tab = nullptr; ra.part_best = nullptr; ra.arrive = nullptr;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
