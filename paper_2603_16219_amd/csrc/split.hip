@@ -214,7 +214,7 @@ __device__ void topk_by_insertion(const TopArgs& a, const void* g, const void* s
 //      candidate buffer in LDS (typically 100-200 entries);
 //   D  each candidate counts the candidates that precede it in the payload order; ranks below k
 //      write themselves to the payload.
-constexpr int kTopSlots = 8;
+constexpr int kTopSlots = 16;  // one vector per group up to 16 K vectors per row
 constexpr int kTopCap = 1024;  // candidate buffer entries; more means a degenerate row -> exact slow path
 constexpr int kTopTodo = 2048; // (lane, group) pairs queued for the exact re-read
 
@@ -347,15 +347,30 @@ __global__ __launch_bounds__(kTopThreads) void cloud_topk_kernel(const TopArgs a
     }
     for (int e = tid; e < ntodo; e += kTopThreads) {
         const int s = todo[e] / kTopThreads, owner = todo[e] % kTopThreads;
-        for (int q = s * gsz; q < min(Q, (s + 1) * gsz); ++q) {
-            const long v = (long)q * kTopThreads + owner;
-            if (v >= nvec) break;
-            float hg[VEC], hm[VEC];
-            unpack(ld_raw<DT, VEC>(g, v), hg);
-            unpack(ld_raw<DT, VEC>(sm, v), hm);
+        const int qend = min(Q, (s + 1) * gsz);
+        for (int q = s * gsz; q < qend; q += 2) {  // two vectors of both rows per round trip
+            typename RawT<DT, VEC>::type rg[2], rm[2];
+            long v[2];
+            bool ok[2];
 #pragma unroll
-            for (int i = 0; i < VEC; ++i)
-                offer(__dsub_rn((double)hg[i], __dmul_rn(a.beta, (double)hm[i])), (int)(v * VEC) + i);
+            for (int j = 0; j < 2; ++j) {
+                v[j] = (long)(q + j) * kTopThreads + owner;
+                ok[j] = q + j < qend && v[j] < nvec;
+                if (ok[j]) {
+                    rg[j] = ld_raw<DT, VEC>(g, v[j]);
+                    rm[j] = ld_raw<DT, VEC>(sm, v[j]);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                if (!ok[j]) continue;
+                float hg[VEC], hm[VEC];
+                unpack(rg[j], hg);
+                unpack(rm[j], hm);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i)
+                    offer(__dsub_rn((double)hg[i], __dmul_rn(a.beta, (double)hm[i])), (int)(v[j] * VEC) + i);
+            }
         }
     }
     if (tid < tailc && tmax >= screen) {
@@ -370,13 +385,27 @@ __global__ __launch_bounds__(kTopThreads) void cloud_topk_kernel(const TopArgs a
         return;
     }
 
-    // ---- D: rank among the candidates = position in the payload
-    if (tid < M) {
-        const double mv = c_v[tid];
-        const int mi = c_i[tid];
-        int rank = 0;
-        for (int u = 0; u < M; ++u) rank += beats(c_v[u], c_i[u], mv, mi) ? 1 : 0;
-        if (rank < topk) {
+    // ---- D: rank among the candidates = position in the payload.  A wave takes every 16th
+    // candidate; its lanes hold the candidate list in registers (the first 256 entries, normally
+    // all of it) and count, together, how many entries precede the wave's candidate.
+    constexpr int kHold = 4;
+    double hv[kHold];
+    int hi[kHold];
+#pragma unroll
+    for (int j = 0; j < kHold; ++j) {
+        const int u = lane + kWave * j;
+        hv[j] = u < M ? c_v[u] : -__builtin_huge_val();
+        hi[j] = u < M ? c_i[u] : 0x7FFFFFFF;
+    }
+    for (int i = wave; i < M; i += kTopWaves) {
+        const double mv = c_v[i];
+        const int mi = c_i[i];
+        int cnt = 0;
+#pragma unroll
+        for (int j = 0; j < kHold; ++j) cnt += beats(hv[j], hi[j], mv, mi) ? 1 : 0;
+        for (int u = lane + kWave * kHold; u < M; u += kWave) cnt += beats(c_v[u], c_i[u], mv, mi) ? 1 : 0;
+        const int rank = wave_sum_i32(cnt);
+        if (lane == 0 && rank < topk) {
             oi[rank] = mi;
             ov[rank] = (float)mv;
         }
