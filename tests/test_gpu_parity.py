@@ -561,3 +561,94 @@ def test_split_recovery_reuses_one_workspace(binding, oracle):
                                    beta=w0.beta, temperature=w0.temperature, want_recovery_logprobs=True, workspace=ws0)
         ora = parity.oracle_run(oracle, inp, lam=w0.lam, beta=w0.beta, temperature=w0.temperature, num_threads=16)
         parity.compare(out, ora, inp["uniforms"], inp["draft_len"])
+
+
+# ------------------------------------------------------------------ every benchmark mode at the size and launch shape bench.py times
+
+@pytest.fixture(scope="module")
+def c4_inputs():
+    w = W.WORKLOADS["c4"]
+    return w, W.generate(w, "cuda")
+
+
+def test_c4_timed_schedule_full_size(binding, oracle, c4_inputs):
+    """The call bench.py times: no per-position log-probs, hence the two-pass schedule, all 256 sequences."""
+    w, inp = c4_inputs
+    p = binding.make_params(w.batch, w.k_max, w.vocab, torch.bfloat16, lam=w.lam, beta=w.beta, temperature=w.temperature)
+    assert binding.first_window(p) == 4
+    out = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], lam=w.lam,
+                               beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"])
+    ora = parity.oracle_run(oracle, inp, lam=w.lam, beta=w.beta, temperature=w.temperature,
+                            want_recovery_logprobs=False, num_threads=16)
+    rep = parity.compare(out, ora, inp["uniforms"], inp["draft_len"])
+    print(f"\n[c4 timed schedule] {rep}", flush=True)
+
+
+def test_c5_timed_schedule_full_size_sampled_sequences(binding, oracle):
+    w = W.WORKLOADS["c5"]
+    inp = W.generate(w, "cuda")
+    out = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], lam=w.lam,
+                               beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"])
+    seqs = torch.arange(3, w.batch, 8, device="cuda")
+    ora = parity.oracle_run(oracle, inp, lam=w.lam, beta=w.beta, temperature=w.temperature, seqs=seqs,
+                            want_recovery_logprobs=False, num_threads=16)
+    parity.compare(out, ora, inp["uniforms"], inp["draft_len"], seqs=seqs)
+    one = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], lam=w.lam,
+                               beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"], full_rows=True)
+    for k in ("accepted_len", "next_token", "next_token_logprob"):
+        assert torch.equal(out[k], one[k]), k  # every sequence: both schedules, bit for bit
+
+
+def test_c4_greedy_full_size(binding, oracle, c4_inputs):
+    w, inp = c4_inputs
+    out = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], lam=w.lam,
+                               beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"], greedy=True)
+    ora = parity.oracle_run(oracle, inp, lam=w.lam, beta=w.beta, temperature=w.temperature, greedy=True,
+                            want_recovery_logprobs=False, num_threads=16)
+    rep = parity.compare(out, ora, inp["uniforms"], inp["draft_len"])
+    assert rep["near_threshold_samples"] == 0
+
+
+def test_c4_cloud_topk_full_size(binding, oracle, c4_inputs):
+    w, inp = c4_inputs
+    row = torch.randint(0, w.k_max + 1, (w.batch,), generator=torch.Generator("cuda").manual_seed(11), device="cuda",
+                        dtype=torch.int32)
+    idx, val = binding.cloud_topk(inp["G"], inp["S_noctx"], row, beta=w.beta, topk=32)
+    sel = torch.arange(0, w.batch, 4, device="cuda")  # 64 of the 256 rows through the oracle's full sort
+    oidx, oval = oracle.cloud_topk(inp["G"][sel].cpu(), inp["S_noctx"][sel].cpu(), row[sel].cpu(), beta=w.beta, topk=32)
+    assert np.array_equal(idx[sel].cpu().numpy(), oidx) and np.array_equal(val[sel].cpu().numpy(), oval)
+    # every row: ordered payload of distinct in-range ids whose values are the exact double logits, rounded
+    assert torch.all((idx >= 0) & (idx < w.vocab))
+    assert torch.all(val[:, :-1] >= val[:, 1:])
+    assert all(len(set(r)) == 32 for r in idx.cpu().tolist())
+    b = torch.arange(w.batch, device="cuda").view(-1, 1).expand(-1, 32)
+    r = row.long().view(-1, 1).expand(-1, 32)
+    g = inp["G"][b, r, idx.long()].double()
+    s = inp["S_noctx"][b, r, idx.long()].double()
+    assert torch.equal((g - float(np.float32(w.beta)) * s).float(), val)
+
+
+@pytest.mark.parametrize("mode", ["steer_rows", "draft_sample"])
+def test_c4_row_modes_full_size_sampled_rows(binding, oracle, c4_inputs, mode):
+    """All 4352 rows of the workload as one-row sequences, as bench.py --mode steer_rows / draft_sample runs them."""
+    w, inp = c4_inputs
+    n = w.batch * (w.k_max + 1)
+    G, Sp, Sm = (inp[k].view(n, w.vocab) for k in ("G", "S_ctx", "S_noctx"))
+    u = inp["uniforms"].reshape(n)
+    if mode == "steer_rows":
+        out = binding.steer_rows(G, Sp, Sm, u, beta=w.beta, temperature=w.temperature)
+        beta = w.beta
+    else:
+        out = binding.sample_rows(Sp, u, temperature=w.temperature)
+        G = Sm = Sp
+        beta = 0.0
+    sel = torch.arange(7, n, 29, device="cuda")  # 150 rows through the oracle
+    m = len(sel)
+    ora = oracle.verify_block(G[sel].view(m, 1, -1).cpu(), Sp[sel].view(m, 1, -1).cpu(), Sm[sel].view(m, 1, -1).cpu(),
+                              torch.zeros(m, 0, dtype=torch.int32), u[sel].view(m, 1).cpu(), beta=beta,
+                              temperature=w.temperature, want_recovery_logprobs=False, num_threads=16)
+    rep = parity.compare({"accepted_len": torch.zeros(m, dtype=torch.int32), "next_token": out["token"][sel],
+                          "next_token_logprob": out["token_logprob"][sel]}, ora, u[sel].view(m, 1), None)
+    print(f"\n[c4 {mode}] {rep}", flush=True)
+    tok = out["token"]
+    assert torch.all((tok >= 0) & (tok < w.vocab))
