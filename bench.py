@@ -103,6 +103,8 @@ def main() -> int:
     ap.add_argument("--workload", default="c4", help="c1..c5 (c4 is the configuration the target is quoted on)")
     ap.add_argument("--sets", type=int, default=2, help="rotating input sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of a HIP graph of the step instead of direct launches (verify modes only)")
     ap.add_argument("--lam", type=float, default=None, help="override the verification threshold")
     ap.add_argument("--mode", default="verify", choices=["verify", "greedy", "steer_rows", "draft_sample", "cloud_topk"],
                     help="verify: the block (default, the headline metric); greedy: same with argmax recovery; "
@@ -182,12 +184,28 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    run = step
+    if args.graph:
+        # the step's launches (kernels only: the library enqueues no memset, copy or allocation) captured once
+        # per input set and replayed: what a launch-bound caller (small batches) would do
+        step(0)
+        torch.cuda.synchronize()
+        graphs = []
+        for j in range(len(sets)):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                step(j)
+            graphs.append(g)
+
+        def run(i):
+            graphs[i % len(sets)].replay()
+
     for i in range(args.warmup):
-        step(i)
+        run(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(i)
+        run(i)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     pos_total = sum(positions[i % len(sets)] for i in range(args.steps))
@@ -241,7 +259,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": describe(w), "mode": args.mode, "logits_dtype": w.dtype, "input_sets": len(sets),
                    "positions_per_step": positions[0], "bonus_fraction": round(bonus_frac, 4),
-                   "first_window": t1, "rows_scored_per_step": round(rows_scored, 1)},
+                   "first_window": t1, "rows_scored_per_step": round(rows_scored, 1),
+                   "launch": "hip graph replay" if args.graph else "direct"},
         "roofline": {
             "bound": "hbm", "kernel": "accept_recover_kernel" if rows_mode else "row_lse_kernel", "achieved": lse_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": lse_gbs / HBM_PEAK_GBS, "traffic": read_traffic(w.name) if args.mode == "verify" else None,

@@ -652,3 +652,41 @@ def test_c4_row_modes_full_size_sampled_rows(binding, oracle, c4_inputs, mode):
     print(f"\n[c4 {mode}] {rep}", flush=True)
     tok = out["token"]
     assert torch.all((tok >= 0) & (tok < w.vocab))
+
+
+# ------------------------------------------------------------------ the block inside a HIP graph
+
+@pytest.mark.parametrize("name,batch", [("c2", 8), ("c4", 40)])
+def test_graph_capture_replays_match_direct_launches(binding, name, batch):
+    """The library enqueues kernels only, so a caller may capture the block in a HIP graph.  Replays with new
+    contents in the same buffers, interleaved with direct launches and synchronisations, must reproduce the
+    direct results bit for bit (the split recovery's arrival counters are cleared inside the graph)."""
+    w = W.scaled(W.WORKLOADS[name], batch=batch, name=f"graph-{name}")
+    inp = W.generate(w, "cuda")
+    p = binding.make_params(w.batch, w.k_max, w.vocab, W.torch_dtype(w.dtype), lam=w.lam, beta=w.beta,
+                            temperature=w.temperature)
+    ws = torch.empty(binding.workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    mk = lambda dt: torch.empty(w.batch, dtype=dt, device="cuda")
+    acc, tok, lp = mk(torch.int32), mk(torch.int32), mk(torch.float32)
+    call = lambda a, t, l, wsp: binding.verify_block_raw(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"],
+                                                         inp["draft_len"], inp["uniforms"], p, a, t, l, None, None, wsp)
+    call(acc, tok, lp, ws)  # warm-up outside the capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        call(acc, tok, lp, ws)
+    ws2 = torch.empty_like(ws)
+    acc2, tok2, lp2 = mk(torch.int32), mk(torch.int32), mk(torch.float32)
+    for rnd in range(4):
+        fresh = W.generate(w, "cuda", seed_shift=rnd + 1)
+        for k in ("G", "S_ctx", "S_noctx", "draft", "uniforms"):
+            inp[k].copy_(fresh[k])
+        if inp["draft_len"] is not None:
+            inp["draft_len"].copy_(fresh["draft_len"])
+        acc.fill_(-7)
+        tok.fill_(-7)
+        g.replay()
+        torch.cuda.synchronize()
+        call(acc2, tok2, lp2, ws2)
+        torch.cuda.synchronize()
+        assert torch.equal(acc, acc2) and torch.equal(tok, tok2) and torch.equal(lp, lp2), rnd
