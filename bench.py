@@ -258,7 +258,8 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": describe(w), "mode": args.mode, "logits_dtype": w.dtype, "input_sets": len(sets),
-                   "positions_per_step": positions[0], "bonus_fraction": round(bonus_frac, 4),
+                   "positions_per_step": positions[0], "rows_per_step": positions[0] + B if not rows_mode else B,
+                   "bonus_fraction": round(bonus_frac, 4),
                    "first_window": t1, "rows_scored_per_step": round(rows_scored, 1),
                    "launch": "hip graph replay" if args.graph else "direct"},
         "roofline": {
