@@ -64,7 +64,8 @@ constexpr float kEClamp = 5.0e8f;           // keeps (int)ceil(h*c) inside int32
 constexpr double kLn2 = 0.693147180559945309417232121458;
 constexpr double kLog2e = 1.442695040888963407359924681002;
 
-constexpr int kRecThreads = 1024;           // accept + recover: one 16-wave workgroup per sequence
+constexpr int kRecThreads = 1024;           // accept + recover: one 16-wave workgroup per sequence ...
+constexpr int kRecThreadsHalf = 512;        // ... or two 8-wave workgroups per CU when sequences outnumber the CUs
 
 struct Partial {
     int E;    // integer exponent reference of this slice
@@ -613,15 +614,15 @@ __device__ __forceinline__ const Partial* partials_of(const RecArgs& a, int b, i
     return a.partial2 + (r * 2 + x) * a.NS2;
 }
 
-// Phase 2 for one sequence by its workgroup of kRecThreads threads, on positions [0, Kt):
+// Phase 2 for one sequence by its workgroup of NT threads, on positions [0, Kt):
 //   2a  every (position, tensor) pair gets a wave: merge its slice partials, gather the draft
 //       token's logit, leave log P(y_t) in lp[2t + x]        (two memory round trips in all)
 //   2b  wave 0: Eq. 7 on every position, first rejection by ballot -> *sh_n (Kt if none)
 // A draft id outside the vocabulary among those positions sets *sh_bad.  Ends with a barrier.
-template <int DT>
+template <int DT, int NT>
 __device__ __forceinline__ void ratio_test_block(const RecArgs& a, int b, int Kt, double* lp, int* sh_n, int* sh_bad) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    constexpr int NW = kRecThreads / kWave;
+    constexpr int NW = NT / kWave;
     const int kmax = a.kmax, V = a.V;
     for (int q = wave; q < 2 * Kt; q += NW) {
         const int t = q >> 1, x = q & 1;
@@ -683,7 +684,7 @@ __global__ __launch_bounds__(kRecThreads) void verdict_kernel(const RecArgs a, i
     }
     __syncthreads();
     const int Kt = sh_bad ? 0 : min(K, a.t1);
-    ratio_test_block<DT>(a, b, Kt, smem_d, &sh_n, &sh_bad);
+    ratio_test_block<DT, kRecThreads>(a, b, Kt, smem_d, &sh_n, &sh_bad);
     if (tid == 0) {
         const bool bad = sh_bad != 0;
         alive[b] = (!bad && sh_n == Kt && K > a.t1) ? 1 : 0;
@@ -720,19 +721,19 @@ __device__ __forceinline__ void wave_best(Best& best) {
 // arrives last (an atomic counter per sequence, no workgroup ever waits for another) runs step 4
 // from the complete table.  The deliveries are made, fenced and counted by one wave, and the
 // last part's reading wave fences before it reads.
-template <int DT, int VEC, bool GREEDY, bool SPLIT, bool PLAIN>
-__global__ __launch_bounds__(kRecThreads) void accept_recover_kernel(const RecArgs a) {
+template <int DT, int VEC, bool GREEDY, bool SPLIT, bool PLAIN, int NT>
+__global__ __launch_bounds__(NT) void accept_recover_kernel(const RecArgs a) {
     extern __shared__ double smem_d[];
     __shared__ int sh_n, sh_bad, sh_last;
     __shared__ double sh_log2Z;
-    __shared__ double sh_best_v[kRecThreads / kWave];
+    __shared__ double sh_best_v[kRecThreads / kWave];  // one slot per wave, or per part in the merge of a split row
     __shared__ long sh_best_i[kRecThreads / kWave];
 
     const int S = SPLIT ? a.parts : 1;
     const int b = SPLIT ? (int)blockIdx.x / S : (int)blockIdx.x;
     const int part = SPLIT ? (int)blockIdx.x - b * S : 0;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    constexpr int NW = kRecThreads / kWave;
+    constexpr int NW = NT / kWave;
     const int kmax = a.kmax, V = a.V;
     double* lp = smem_d;                                            // [kmax][2] log P_LLM, log P_SLM^-
     Partial* tab = reinterpret_cast<Partial*>(smem_d + 2 * kmax);   // [NC] chunk masses
@@ -749,11 +750,11 @@ __global__ __launch_bounds__(kRecThreads) void accept_recover_kernel(const RecAr
         sh_n = settled ? a.first_rej[b] : 0;
     }
     __syncthreads();
-    if (!settled) ratio_test_block<DT>(a, b, Kt, lp, &sh_n, &sh_bad);
+    if (!settled) ratio_test_block<DT, NT>(a, b, Kt, lp, &sh_n, &sh_bad);
     const bool bad = sh_bad != 0;
     if (a.draft_logprobs && part == 0) {  // valid positions from LDS, padded slots 0, a flagged sequence NaN throughout
         const float nanv = __int_as_float(0x7FC00000);
-        for (int i = tid; i < kmax * 2; i += kRecThreads)
+        for (int i = tid; i < kmax * 2; i += NT)
             a.draft_logprobs[(long)b * kmax * 2 + i] = bad ? nanv : (i < 2 * Kt ? (float)lp[i] : 0.f);
     }
     if (bad) {
@@ -835,7 +836,7 @@ __global__ __launch_bounds__(kRecThreads) void accept_recover_kernel(const RecAr
         __syncthreads();
         const double log2Z = sh_log2Z;
         float* out = a.recovery_logprobs + (long)b * V;
-        for (long v = tid; v < nvec; v += kRecThreads) {
+        for (long v = tid; v < nvec; v += NT) {
             float hg[VEC], hp[VEC], hm[VEC];
             unpack(ld_raw<DT, VEC>(g, v), hg);
             if (PLAIN) {
@@ -1062,13 +1063,23 @@ hipError_t launch_all(LseArgs la, RecArgs ra, const Plan& pl, char* ws, hipStrea
     // accept + recover: LDS holds the per-position log-probs and one mass per recovery chunk
     const dim3 rec_grid((unsigned)(B * ra.parts));
     using RecKernel = void (*)(RecArgs);
+    constexpr int kFull = kRecThreads, kHalf = kRecThreadsHalf;
     static const RecKernel rec_kernels[8] = {  // index: greedy | split << 1 | plain << 2
-        accept_recover_kernel<DT, VEC, false, false, false>, accept_recover_kernel<DT, VEC, true, false, false>,
-        accept_recover_kernel<DT, VEC, false, true, false>,  accept_recover_kernel<DT, VEC, true, true, false>,
-        accept_recover_kernel<DT, VEC, false, false, true>,  accept_recover_kernel<DT, VEC, true, false, true>,
-        accept_recover_kernel<DT, VEC, false, true, true>,   accept_recover_kernel<DT, VEC, true, true, true>};
-    hipLaunchKernelGGL(rec_kernels[(ra.greedy ? 1 : 0) | (split ? 2 : 0) | (ra.plain ? 4 : 0)], rec_grid,
-                       dim3(kRecThreads), smem, stream, ra);
+        accept_recover_kernel<DT, VEC, false, false, false, kFull>, accept_recover_kernel<DT, VEC, true, false, false, kFull>,
+        accept_recover_kernel<DT, VEC, false, true, false, kFull>,  accept_recover_kernel<DT, VEC, true, true, false, kFull>,
+        accept_recover_kernel<DT, VEC, false, false, true, kFull>,  accept_recover_kernel<DT, VEC, true, false, true, kFull>,
+        accept_recover_kernel<DT, VEC, false, true, true, kFull>,   accept_recover_kernel<DT, VEC, true, true, true, kFull>};
+    // With at least two sequences per compute unit, two 8-wave workgroups share a unit: the serial ends of one
+    // sequence (ratio test, token pick) then overlap the sweep of another.  Same waves per unit, same arithmetic.
+    static const RecKernel rec_kernels_half[4] = {  // index: greedy | plain << 1
+        accept_recover_kernel<DT, VEC, false, false, false, kHalf>, accept_recover_kernel<DT, VEC, true, false, false, kHalf>,
+        accept_recover_kernel<DT, VEC, false, false, true, kHalf>,  accept_recover_kernel<DT, VEC, true, false, true, kHalf>};
+    if (!split && B >= 2 * kChipCus)
+        hipLaunchKernelGGL(rec_kernels_half[(ra.greedy ? 1 : 0) | (ra.plain ? 2 : 0)], rec_grid, dim3(kHalf), smem,
+                           stream, ra);
+    else
+        hipLaunchKernelGGL(rec_kernels[(ra.greedy ? 1 : 0) | (split ? 2 : 0) | (ra.plain ? 4 : 0)], rec_grid,
+                           dim3(kFull), smem, stream, ra);
     mark(4);
     const hipError_t launch_err = hipGetLastError();
     return launch_err != hipSuccess ? launch_err : ev_err;
