@@ -690,3 +690,14 @@ def test_graph_capture_replays_match_direct_launches(binding, name, batch):
         call(acc2, tok2, lp2, ws2)
         torch.cuda.synchronize()
         assert torch.equal(acc, acc2) and torch.equal(tok, tok2) and torch.equal(lp, lp2), rnd
+
+
+@pytest.mark.parametrize("temperature,beta", [(0.05, 1.0), (0.01, -0.7), (25.0, 3.0), (1e-3, 0.5)])
+def test_temperature_and_beta_extremes(binding, oracle, temperature, beta):
+    """Near-deterministic rows (tiny T: exponents in the thousands, one token carries the row), nearly flat rows
+    (large T: every token matters, the CDF walk crosses many chunks) and a negative steering strength."""
+    import dataclasses
+    w = dataclasses.replace(W.scaled(W.WORKLOADS["c4"], batch=20, vocab=40000, k_max=6, name=f"T{temperature}"),
+                            temperature=temperature, beta=beta)
+    inp = W.generate(w, "cuda")
+    run_both(binding, oracle, w, inp)
