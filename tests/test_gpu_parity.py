@@ -701,3 +701,25 @@ def test_temperature_and_beta_extremes(binding, oracle, temperature, beta):
                             temperature=temperature, beta=beta)
     inp = W.generate(w, "cuda")
     run_both(binding, oracle, w, inp)
+
+
+@pytest.mark.parametrize("greedy", [False, True])
+@pytest.mark.parametrize("beta", [0.0, 1.2])
+@pytest.mark.parametrize("dtype,vocab", [("bf16", 9000), ("f32", 5003)])
+def test_many_sequences_use_half_size_workgroups(binding, oracle, greedy, beta, dtype, vocab):
+    """B >= 512 runs the recovery with two 8-wave workgroups per compute unit: every variant of that kernel
+    (sampled / greedy, steered / beta = 0, vector / element-wise loads), with flagged sequences in the batch."""
+    import dataclasses
+    w = dataclasses.replace(W.scaled(W.WORKLOADS["c4"], batch=600, vocab=vocab, k_max=5, name=f"half-{dtype}-{beta}-{greedy}"),
+                            dtype=dtype, beta=beta)
+    inp = W.generate(w, "cuda")
+    inp["draft_len"][17] = 6
+    inp["draft"][300, 0] = vocab
+    inp["draft_len"][300] = max(1, int(inp["draft_len"][300]))
+    out = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], lam=w.lam,
+                               beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"],
+                               want_recovery_logprobs=True, want_draft_logprobs=True, greedy=greedy)
+    ora = parity.oracle_run(oracle, inp, lam=w.lam, beta=w.beta, temperature=w.temperature, greedy=greedy, num_threads=16)
+    rep = parity.compare(out, ora, inp["uniforms"], inp["draft_len"])
+    assert out["accepted_len"][17].item() == -1 and out["accepted_len"][300].item() == -1
+    assert rep["unexcused_mismatches"] == 0
