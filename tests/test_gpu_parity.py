@@ -723,3 +723,30 @@ def test_many_sequences_use_half_size_workgroups(binding, oracle, greedy, beta, 
     rep = parity.compare(out, ora, inp["uniforms"], inp["draft_len"])
     assert out["accepted_len"][17].item() == -1 and out["accepted_len"][300].item() == -1
     assert rep["unexcused_mismatches"] == 0
+
+
+# ------------------------------------------------------------------ properties that hold at any size
+
+@pytest.mark.parametrize("name", ["c2", "c4"])
+def test_sequences_are_independent_of_their_place_in_the_batch(binding, name):
+    """Every sequence is verified on its own: shuffling the batch shuffles the outputs, bit for bit (nothing a
+    sequence produces may depend on which workgroups, slices or passes its neighbours happened to get)."""
+    w = W.WORKLOADS[name]
+    inp = W.generate(w, "cuda")
+    call = lambda d: binding.verify_block(d["G"], d["S_ctx"], d["S_noctx"], d["draft"], d["uniforms"], lam=w.lam,
+                                          beta=w.beta, temperature=w.temperature, draft_len=d["draft_len"],
+                                          want_recovery_logprobs=(name == "c2"))
+    ref = call(inp)
+    perm = torch.randperm(w.batch, generator=torch.Generator("cuda").manual_seed(99), device="cuda")
+    shuf = {k: (None if v is None else v[perm].contiguous()) for k, v in inp.items()}
+    del inp
+    got = call(shuf)
+    for k in ("accepted_len", "next_token", "next_token_logprob", "recovery_logprobs"):
+        if ref[k] is not None:
+            assert torch.equal(ref[k][perm], got[k]), k
+    # and a sequence alone gives what it gave inside the batch
+    one = {k: (None if v is None else v[3:4].contiguous()) for k, v in shuf.items()}
+    solo = call(one)
+    for k in ("accepted_len", "next_token"):
+        assert torch.equal(solo[k], got[k][3:4]), k
+    assert abs(solo["next_token_logprob"].item() - got["next_token_logprob"][3].item()) <= 2e-6

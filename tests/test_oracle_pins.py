@@ -542,3 +542,43 @@ def test_edge_resample_law_and_truncation(oracle):
     # flagged sequence
     e = oracle.edge_resample(idx, val, Sp, np.array([-1], np.int32), np.array([0.3], np.float32))
     assert e["next_token"][0] == -1 and np.isnan(e["next_token_logprob"][0])
+
+
+# ---------------------------------------------------------------- structure of the loop (Algorithm 1)
+
+def test_a_block_equals_its_two_halves_verified_in_turn(oracle):
+    """Algorithm 1 walks the positions in order and stops at the first rejection, so verifying K drafted
+    tokens at once must agree with verifying the first K1 and, only if all of them pass, the remaining
+    K - K1 on the rows that follow (row t scores draft token t; the row after the last accepted token
+    yields the correction or bonus token)."""
+    rng = np.random.default_rng(41)
+    B, K, K1, V = 48, 7, 3, 23
+    G, Sp, Sm, d, u = rand_block(rng, B, K, V, scale=1.2)
+    whole = oracle.verify_block(G, Sp, Sm, d, u, lam=0.6, beta=0.9, temperature=1.1)
+    # first half: rows 0..K1 (K1 draft rows + the row after them), same sampling uniform
+    u1 = np.concatenate([u[:, :K1], u[:, -1:]], axis=1)
+    first = oracle.verify_block(G[:, :K1 + 1], Sp[:, :K1 + 1], Sm[:, :K1 + 1], d[:, :K1], u1, lam=0.6, beta=0.9,
+                                temperature=1.1)
+    u2 = np.concatenate([u[:, K1:K], u[:, -1:]], axis=1)
+    second = oracle.verify_block(G[:, K1:], Sp[:, K1:], Sm[:, K1:], d[:, K1:], u2, lam=0.6, beta=0.9, temperature=1.1)
+    seen = set()
+    for b in range(B):
+        if first["accepted_len"][b] < K1:
+            n, tok = first["accepted_len"][b], first["next_token"][b]
+            seen.add("early")
+        else:
+            n, tok = K1 + second["accepted_len"][b], second["next_token"][b]
+            seen.add("late")
+        assert whole["accepted_len"][b] == n and whole["next_token"][b] == tok
+    assert seen == {"early", "late"}
+
+
+def test_sequences_do_not_interact(oracle):
+    rng = np.random.default_rng(42)
+    G, Sp, Sm, d, u = rand_block(rng, 9, 4, 31)
+    dl = rng.integers(0, 5, 9).astype(np.int32)
+    ref = oracle.verify_block(G, Sp, Sm, d, u, draft_len=dl, beta=1.4)
+    perm = rng.permutation(9)
+    got = oracle.verify_block(G[perm], Sp[perm], Sm[perm], d[perm], u[perm], draft_len=dl[perm], beta=1.4)
+    for k in ("accepted_len", "next_token", "next_token_logprob", "recovery_logprobs"):
+        assert np.array_equal(ref[k][perm], got[k]), k
