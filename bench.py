@@ -103,6 +103,8 @@ def main() -> int:
     ap.add_argument("--workload", default="c4", help="c1..c5 (c4 is the configuration the target is quoted on)")
     ap.add_argument("--sets", type=int, default=2, help="rotating input sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--dtype", choices=["bf16", "f32"], default=None,
+                    help="store the workload's logits in this type instead of its own (same recipe, rounded to it)")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of a HIP graph of the step instead of direct launches (verify modes only)")
     ap.add_argument("--lam", type=float, default=None, help="override the verification threshold")
@@ -136,6 +138,9 @@ def main() -> int:
     if args.lam is not None:
         import dataclasses
         w = dataclasses.replace(w, lam=args.lam)
+    if args.dtype is not None and args.dtype != w.dtype:
+        import dataclasses
+        w = dataclasses.replace(w, dtype=args.dtype, name=f"{w.name}@{args.dtype}")
     esz = 2 if w.dtype == "bf16" else 4
 
     sets = [W.generate(w, dev, seed_shift=i) for i in range(max(1, args.sets))]
