@@ -38,8 +38,15 @@ class _Params(ctypes.Structure):
     ]
 
 
+# The pin suite's mutation test points this at deliberately wrong builds of the oracle to show that
+# the pins notice; nothing else sets it.
+_LIB_OVERRIDE = os.environ.get("SPECSTEER_ORACLE_LIBRARY")
+
+
 def build(force: bool = False) -> str:
     """Compile the C oracle into a shared library next to its source."""
+    if _LIB_OVERRIDE:
+        return _LIB_OVERRIDE
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)

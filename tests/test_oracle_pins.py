@@ -544,6 +544,23 @@ def test_edge_resample_law_and_truncation(oracle):
     assert e["next_token"][0] == -1 and np.isnan(e["next_token_logprob"][0])
 
 
+def test_edge_resample_on_an_exact_cdf_edge(oracle):
+    """Equal candidates make the k-way CDF exactly 1/k, 2/k, ... (k a power of two): a uniform that sits exactly
+    on an edge belongs to the NEXT candidate, because the draw takes the first inclusive cumulative
+    probability that exceeds it -- the same strict rule as the full-vocabulary draw."""
+    V = 16
+    G = np.full((1, 1, V), -30.0, np.float32)
+    G[0, 0, [3, 7, 9, 12]] = 0.0          # four equal leaders at 0, so that log-sum-exp is exactly log 4
+    Z = np.zeros_like(G)
+    row = np.zeros(1, np.int32)
+    idx, val = oracle.cloud_topk(G, Z, row, beta=1.0, topk=4)
+    assert idx[0].tolist() == [3, 7, 9, 12]
+    for us, want in [(0.0, 3), (0.25, 7), (0.5, 9), (0.75, 12), (0.24999999, 3), (0.4999999, 7)]:
+        e = oracle.edge_resample(idx, val, Z, row, np.array([us], np.float32), beta=1.0, temperature=1.0)
+        assert e["next_token"][0] == want, (us, e["next_token"][0])
+        assert e["next_token_logprob"][0] == pytest.approx(np.log(0.25), abs=1e-15)
+
+
 # ---------------------------------------------------------------- structure of the loop (Algorithm 1)
 
 def test_a_block_equals_its_two_halves_verified_in_turn(oracle):
