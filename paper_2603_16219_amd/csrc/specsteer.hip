@@ -875,16 +875,15 @@ struct Plan {
 };
 
 // Small batches split each sequence's recovery row over several workgroups so that the sweep is
-// not tied to the rate of one compute unit per sequence.  The chip has 256 compute units; a part
-// is worth having only if it gets a full round of 16 chunks.
-constexpr int kSplitMaxBatch = 128;
-constexpr int kSplitMaxParts = 16;  // one LDS slot per part in the greedy merge
-constexpr int kChipCus = 256;
+// not tied to the rate of one compute unit per sequence: as many parts as there are compute units
+// per sequence, but a part is worth having only if it gets a full round of 16 chunks.
+constexpr int kSplitMaxBatch = 128;  // workspace is reserved for the split up to this batch (half of MI355X's 256 units)
+constexpr int kSplitMaxParts = 16;   // one LDS slot per part in the greedy merge
 
-int recovery_parts(int B, int NC) {
+int recovery_parts(int B, int NC, int cus) {
     if (B < 1 || B > kSplitMaxBatch) return 1;
     const int by_chunks = (NC + (kRecThreads / kWave) - 1) / (kRecThreads / kWave);
-    int parts = kChipCus / B;
+    int parts = cus / B;
     if (parts > by_chunks) parts = by_chunks;
     if (parts > kSplitMaxParts) parts = kSplitMaxParts;
     return parts < 1 ? 1 : parts;
@@ -1032,7 +1031,8 @@ hipError_t launch_all(LseArgs la, RecArgs ra, const Plan& pl, char* ws, hipStrea
     ra.flagged = two_pass ? flagged : nullptr;
     ra.first_rej = two_pass ? first_rej : nullptr;
     ra.NC = chunks_per_row(V, VEC);
-    ra.parts = recovery_parts(B, ra.NC);
+    const int cus = device_cu_count();
+    ra.parts = recovery_parts(B, ra.NC, cus);
     ra.arrive = reinterpret_cast<uint32_t*>(ws + pl.off_arrive);
     ra.part_best = reinterpret_cast<Best*>(ws + pl.off_part_best);
     ra.chunk_tab = reinterpret_cast<Partial*>(ws + pl.off_chunk_tab);
@@ -1074,7 +1074,7 @@ hipError_t launch_all(LseArgs la, RecArgs ra, const Plan& pl, char* ws, hipStrea
     static const RecKernel rec_kernels_half[4] = {  // index: greedy | plain << 1
         accept_recover_kernel<DT, VEC, false, false, false, kHalf>, accept_recover_kernel<DT, VEC, true, false, false, kHalf>,
         accept_recover_kernel<DT, VEC, false, false, true, kHalf>,  accept_recover_kernel<DT, VEC, true, false, true, kHalf>};
-    if (!split && B >= 2 * kChipCus)
+    if (!split && B >= 2 * cus)
         hipLaunchKernelGGL(rec_kernels_half[(ra.greedy ? 1 : 0) | (ra.plain ? 2 : 0)], rec_grid, dim3(kHalf), smem,
                            stream, ra);
     else
