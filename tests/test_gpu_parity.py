@@ -750,3 +750,19 @@ def test_sequences_are_independent_of_their_place_in_the_batch(binding, name):
     for k in ("accepted_len", "next_token"):
         assert torch.equal(solo[k], got[k][3:4]), k
     assert abs(solo["next_token_logprob"].item() - got["next_token_logprob"][3].item()) <= 2e-6
+
+
+@pytest.mark.parametrize("lam", [1e-30, 1e30, 3.0])
+def test_threshold_extremes(binding, oracle, lam):
+    """A vanishing threshold accepts every draft token (exp overflows to inf before the min), a huge one rejects at
+    the first position; both sides must still agree on the recovery token."""
+    import dataclasses
+    w = dataclasses.replace(W.scaled(W.WORKLOADS["c4"], batch=24, vocab=20000, k_max=6, name=f"lam{lam}"), lam=lam)
+    inp = W.generate(w, "cuda")
+    inp["uniforms"].clamp_(min=1e-3)
+    out, ora, rep = run_both(binding, oracle, w, inp)
+    n = out["accepted_len"].cpu()
+    if lam == 1e-30:
+        assert torch.equal(n, inp["draft_len"].cpu())
+    if lam == 1e30:
+        assert torch.all(n[inp["draft_len"].cpu() > 0] == 0)
