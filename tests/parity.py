@@ -16,7 +16,9 @@ NEAR = 1e-6
 
 
 def _np(x):
-    return None if x is None else x.detach().cpu().numpy()
+    if x is None or isinstance(x, np.ndarray):
+        return x
+    return x.detach().cpu().numpy()
 
 
 def oracle_run(oracle, inp, *, lam, beta, temperature, seqs=None, want_recovery_logprobs=True, num_threads=8,

@@ -158,3 +158,23 @@ def test_first_window(B):
     assert B.first_window(B.make_params(8, 8, 151936, torch.bfloat16, lam=0.5, beta=1.0, temperature=1.0)) == 8   # small batch
     assert B.first_window(B.make_params(512, 3, 256000, torch.bfloat16, lam=0.5, beta=1.0, temperature=1.0)) == 3  # short block
     assert B.first_window(B.make_params(-1, 3, 10, torch.bfloat16, lam=0.5, beta=1.0, temperature=1.0)) == -1
+
+
+def test_header_is_plain_c():
+    """The boundary is a C ABI: the header must compile as C99 and as C++ on its own."""
+    import subprocess
+
+    hdr = os.path.join(ROOT, "include", "specsteer.h")
+    for lang, std in (("c", "-std=c99"), ("c++", "-std=c++11")):
+        r = subprocess.run(["gcc", "-x", lang, std, "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", hdr],
+                           capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
+
+
+def test_plain_c_client_builds_against_the_library(lib):
+    import sys
+
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    import abi_client
+
+    assert os.path.exists(abi_client.build())

@@ -766,3 +766,40 @@ def test_threshold_extremes(binding, oracle, lam):
         assert torch.equal(n, inp["draft_len"].cpu())
     if lam == 1e30:
         assert torch.all(n[inp["draft_len"].cpu() > 0] == 0)
+
+
+# ------------------------------------------------------------------ the boundary from plain C
+
+def test_plain_c_caller_without_python_or_torch(binding, oracle, tmp_path):
+    """A C99 program (tests/abi_client) stages one block with hipMalloc / hipMemcpy, calls the library and
+    writes the outputs to a file: they must be what the oracle says, and bit-identical to the binding's."""
+    import subprocess
+    import sys
+
+    sys.path.insert(0, str(__import__("pathlib").Path(__file__).parent))
+    import abi_client
+
+    exe = abi_client.build()
+    w = W.scaled(W.WORKLOADS["c4"], batch=9, vocab=50000, k_max=6, name="c-client")
+    inp = W.generate(w, "cuda")
+    blob = tmp_path / "in.bin"
+    with open(blob, "wb") as f:
+        f.write(np.array([w.batch, w.k_max, w.vocab, 1, 1], np.int32).tobytes())
+        f.write(np.array([w.lam, w.beta, w.temperature], np.float32).tobytes())
+        for k in ("G", "S_ctx", "S_noctx"):
+            f.write(inp[k].contiguous().view(torch.int16).cpu().numpy().tobytes())
+        f.write(inp["draft"].cpu().numpy().astype(np.int32).tobytes())
+        f.write(inp["draft_len"].cpu().numpy().astype(np.int32).tobytes())
+        f.write(inp["uniforms"].cpu().numpy().astype(np.float32).tobytes())
+    outp = tmp_path / "out.bin"
+    r = subprocess.run([exe, str(blob), str(outp)], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stderr
+    raw = np.fromfile(outp, dtype=np.int32)
+    B = w.batch
+    got = {"accepted_len": raw[:B], "next_token": raw[B:2 * B], "next_token_logprob": raw[2 * B:3 * B].view(np.float32)}
+    ora = parity.oracle_run(oracle, inp, lam=w.lam, beta=w.beta, temperature=w.temperature, want_recovery_logprobs=False)
+    parity.compare(got, ora, inp["uniforms"], inp["draft_len"])
+    ref = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], lam=w.lam,
+                               beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"])
+    for k in got:
+        assert np.array_equal(ref[k].cpu().numpy().view(np.int32), np.asarray(got[k]).view(np.int32)), k
