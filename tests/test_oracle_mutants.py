@@ -71,4 +71,6 @@ def test_pins_catch_a_planted_mistake(tmp_path, source_text, what, old, new):
     run = subprocess.run([sys.executable, "-m", "pytest", os.path.join(HERE, "test_oracle_pins.py"), "-x", "-q",
                           "-p", "no:cacheprovider"], cwd=ROOT, env=env, capture_output=True, text=True, timeout=600)
     assert run.returncode != 0, f"no pin noticed: {what}"
-    assert "failed" in run.stdout or "error" in run.stdout.lower(), run.stdout[-400:]
+    # 1 = a pin failed; a mutant that indexes out of bounds may also take the child down with a signal.
+    # Anything else (no tests collected, usage error) would be this test's own fault.
+    assert run.returncode == 1 or run.returncode < 0 or run.returncode in (134, 139), (run.returncode, run.stderr[-400:])
