@@ -303,9 +303,15 @@ def main() -> int:
                                       want_recovery_logprobs=False, num_threads=threads, greedy=args.mode == "greedy")
             walls.append(time.perf_counter() - t1)
         cpu_s = sorted(walls)[len(walls) // 2]
+        t1 = time.perf_counter()  # and one pass on a single thread
+        oracle.verify_block(host["G"], host["S_ctx"], host["S_noctx"], host["draft"], host["uniforms"],
+                            lam=w.lam, beta=w.beta, temperature=w.temperature, draft_len=host["draft_len"],
+                            want_recovery_logprobs=False, num_threads=1, greedy=args.mode == "greedy")
+        cpu_1 = time.perf_counter() - t1
         cpu_pos = int(host["draft_len"].sum().item()) if host["draft_len"] is not None else nseq * kmax
         out["cpu_baseline"] = {
             "value": cpu_pos / cpu_s, "unit": "positions/s", "cores": threads, "kind": "oracle",
+            "value_one_thread": cpu_pos / cpu_1,
             "sample": f"first {nseq} of {B} sequences of {w.name} ({cpu_pos} positions), float64 oracle, "
                       f"{threads} OpenMP threads over sequences, median of {len(walls)} passes of {cpu_s:.3f} s wall "
                       f"({sum(walls) * threads:.0f} CPU-seconds in all)",
