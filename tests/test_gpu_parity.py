@@ -803,3 +803,19 @@ def test_plain_c_caller_without_python_or_torch(binding, oracle, tmp_path):
                                beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"])
     for k in got:
         assert np.array_equal(ref[k].cpu().numpy().view(np.int32), np.asarray(got[k]).view(np.int32)), k
+
+
+def test_a_uniform_of_one_on_gpu(binding, oracle):
+    """Out of contract (uniforms are promised below 1) but harmless: the draw falls back to the last token that has
+    any probability, on a row whose tail has none, in the first chunk and across chunks."""
+    for V, hot in ((6, [1, 3]), (5000, [17, 4100]), (70000, [5, 65000])):
+        G = torch.full((1, 1, V), -1.0e4, dtype=torch.float32, device="cuda")
+        G[0, 0, hot] = 0.0
+        Z = torch.zeros_like(G)
+        d = torch.zeros(1, 0, dtype=torch.int32, device="cuda")
+        for us in (1.0, 0.0):
+            u = torch.tensor([[us]], dtype=torch.float32, device="cuda")
+            out = binding.verify_block(G, Z, Z, d, u)
+            ora = oracle.verify_block(G.cpu(), Z.cpu(), Z.cpu(), d.cpu(), u.cpu())
+            assert out["next_token"].item() == ora["next_token"][0] == (hot[1] if us == 1.0 else hot[0])
+            assert abs(out["next_token_logprob"].item() - np.log(0.5)) < 1e-6

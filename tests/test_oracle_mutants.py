@@ -38,6 +38,7 @@ MUTANTS = [
     ("uniforms indexed with the draft's row length", "uniforms + (size_t)b * (kmax + 1)", "uniforms + (size_t)b * (kmax)"),
     ("draft indexed with the logits' row count", "draft + (size_t)b * kmax, K", "draft + (size_t)b * (kmax+1), K"),
     ("longest allowed draft flagged", "K > kmax", "K >= kmax"),
+    ("fallback token may have no probability", "if (pv > 0.0) last_pos = v;", "last_pos = v;"),
     ("greedy pick keeps the last maximum", "if (hrec > hmax) {", "if (hrec >= hmax) {"),
     ("greedy pick ignores the steering term", "if (hrec > hmax) {", "if (hl > hmax) {"),
     ("bonus row confused with the last draft row", "int n = K;\n    for (int t = 0; t < K; ++t) {", "int n = K > 0 ? K - 1 : 0;\n    for (int t = 0; t < K; ++t) {"),

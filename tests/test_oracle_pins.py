@@ -561,6 +561,20 @@ def test_edge_resample_on_an_exact_cdf_edge(oracle):
         assert e["next_token_logprob"][0] == pytest.approx(np.log(0.25), abs=1e-15)
 
 
+def test_a_uniform_of_one_returns_the_last_token_with_probability(oracle):
+    """uniforms are promised in [0, 1); a value of exactly 1 is not below any cumulative probability, and the
+    draw then falls back to the last token that has any probability at all (never to one with none)."""
+    V = 6
+    G = np.full((1, 1, V), -1.0e4, np.float32)
+    G[0, 0, 1] = G[0, 0, 3] = 0.0  # p = (0, 1/2, 0, 1/2, 0, 0) exactly: the CDF ends at exactly 1
+    Z = np.zeros_like(G)
+    d = np.zeros((1, 0), np.int32)
+    for us, want in [(1.0, 3), (0.5, 3), (0.49999997, 1), (0.0, 1)]:
+        r = oracle.verify_block(G, Z, Z, d, np.array([[us]], np.float32))
+        assert r["next_token"][0] == want, (us, r["next_token"][0])
+        assert r["next_token_logprob"][0] == pytest.approx(np.log(0.5), abs=1e-15)
+
+
 # ---------------------------------------------------------------- structure of the loop (Algorithm 1)
 
 def test_a_block_equals_its_two_halves_verified_in_turn(oracle):
