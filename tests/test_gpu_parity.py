@@ -819,3 +819,18 @@ def test_a_uniform_of_one_on_gpu(binding, oracle):
             ora = oracle.verify_block(G.cpu(), Z.cpu(), Z.cpu(), d.cpu(), u.cpu())
             assert out["next_token"].item() == ora["next_token"][0] == (hot[1] if us == 1.0 else hot[0])
             assert abs(out["next_token_logprob"].item() - np.log(0.5)) < 1e-6
+
+
+def test_edge_resample_with_a_uniform_of_one_on_gpu(binding, oracle):
+    V = 12
+    G = torch.full((1, 1, V), -3.0e4, dtype=torch.float32, device="cuda")
+    G[0, 0, [2, 9]] = 0.0
+    G[0, 0, [4, 5]] = -1.0e4
+    Z = torch.zeros_like(G)
+    row = torch.zeros(1, dtype=torch.int32, device="cuda")
+    idx, val = binding.cloud_topk(G, Z, row, beta=1.0, topk=4)
+    assert idx[0].cpu().tolist() == [2, 9, 4, 5]
+    for us, want in [(1.0, 9), (0.75, 9), (0.25, 2)]:
+        out = binding.edge_resample(idx, val, Z, row, torch.tensor([us], dtype=torch.float32, device="cuda"), beta=1.0,
+                                    temperature=1.0)
+        assert out["next_token"].item() == want, (us, out["next_token"].item())

@@ -50,6 +50,7 @@ MUTANTS = [
      "if (a->v > b->v) return 1;\n    if (a->v < b->v) return -1;"),
     ("edge side forgets beta", "(double)vl[j] + beta * widen(S_ctx, dt, off + ix[j])", "(double)vl[j] + widen(S_ctx, dt, off + ix[j])"),
     ("edge side ignores the temperature", "x[j] = h[j] / T;", "x[j] = h[j];"),
+    ("edge side falls back to an entry without probability", "if (pj > 0.0) last_pos = j;", "last_pos = j;"),
     ("edge side draws with a non-strict comparison", "c > (double)uniform[b]", "c >= (double)uniform[b]"),
 ]
 

@@ -561,6 +561,21 @@ def test_edge_resample_on_an_exact_cdf_edge(oracle):
         assert e["next_token_logprob"][0] == pytest.approx(np.log(0.25), abs=1e-15)
 
 
+def test_edge_resample_with_a_uniform_of_one(oracle):
+    """Same fallback on the edge side: the last payload entry that has any probability."""
+    V = 12
+    G = np.full((1, 1, V), -3.0e4, np.float32)
+    G[0, 0, [2, 9]] = 0.0
+    G[0, 0, [4, 5]] = -1.0e4          # in the payload, but with no probability next to the leaders
+    Z = np.zeros_like(G)
+    row = np.zeros(1, np.int32)
+    idx, val = oracle.cloud_topk(G, Z, row, beta=1.0, topk=4)
+    assert idx[0].tolist() == [2, 9, 4, 5]
+    for us, want in [(1.0, 9), (0.5, 9), (0.25, 2)]:
+        e = oracle.edge_resample(idx, val, Z, row, np.array([us], np.float32), beta=1.0, temperature=1.0)
+        assert e["next_token"][0] == want, (us, e["next_token"][0])
+
+
 def test_a_uniform_of_one_returns_the_last_token_with_probability(oracle):
     """uniforms are promised in [0, 1); a value of exactly 1 is not below any cumulative probability, and the
     draw then falls back to the last token that has any probability at all (never to one with none)."""
