@@ -140,8 +140,10 @@ size_t specsteer_workspace_bytes(const ss_params *params);
  * for some t < K_b -- mark that sequence alone: accepted_len[b] =
  * next_token[b] = -1, next_token_logprob[b] and its draft_logprobs are NaN, its
  * recovery_logprobs row is left unwritten; no out-of-range address is ever
- * formed.  Logits on rows that are read must be finite (behaviour with NaN or
- * infinities there is unspecified but never faults).
+ * formed.  A logit of -inf in G masks that token for the generalist: probability
+ * zero, rejected if drafted, never drawn or picked.  Otherwise logits on rows that
+ * are read must be finite (behaviour with NaN, +inf, or -inf in S_ctx / S_noctx is
+ * unspecified but never faults).
  */
 ss_status specsteer_verify_block(const void *G, const void *S_ctx, const void *S_noctx,
                                  const int32_t *draft, const int32_t *draft_len,

@@ -834,3 +834,32 @@ def test_edge_resample_with_a_uniform_of_one_on_gpu(binding, oracle):
         out = binding.edge_resample(idx, val, Z, row, torch.tensor([us], dtype=torch.float32, device="cuda"), beta=1.0,
                                     temperature=1.0)
         assert out["next_token"].item() == want, (us, out["next_token"].item())
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_tokens_masked_by_the_generalist(binding, oracle, dtype):
+    """-inf in G (a logits processor masked the token for the verifier) is probability zero: such a draft token
+    is rejected, such a token is never drawn or picked, and everything else is as usual."""
+    import dataclasses
+    w = dataclasses.replace(W.scaled(W.WORKLOADS["c4"], batch=24, vocab=30000, k_max=6, name=f"masked-{dtype}"), dtype=dtype)
+    inp = W.generate(w, "cuda")
+    mask = torch.rand(inp["G"].shape, device="cuda", generator=torch.Generator("cuda").manual_seed(4)) < 0.3
+    mask[:, :, 1000:1100] = True            # whole 16-byte vectors and a whole stretch masked
+    inp["G"][mask] = float("-inf")
+    out, ora, rep = run_both(binding, oracle, w, inp)
+    tok = out["next_token"].long()
+    n = out["accepted_len"].long()
+    b = torch.arange(w.batch, device="cuda")
+    assert torch.all(torch.isfinite(inp["G"][b, n, tok].float()))          # never a masked token
+    lp = out["recovery_logprobs"]
+    assert torch.all(lp[mask[b, n]] == float("-inf"))
+    assert torch.allclose(torch.exp(lp.double()).sum(-1), torch.ones(w.batch, dtype=torch.float64, device="cuda"), atol=1e-5)
+    # a masked draft token is rejected on the spot (its uniform is positive)
+    d0 = inp["draft"][:, 0].long()
+    masked_first = mask[b, 0, d0] & (inp["draft_len"] > 0) & (inp["uniforms"][:, 0] > 0)
+    assert torch.all(n[masked_first] == 0) and masked_first.any()
+    g = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], lam=w.lam,
+                             beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"], greedy=True)
+    og = parity.oracle_run(oracle, inp, lam=w.lam, beta=w.beta, temperature=w.temperature, greedy=True,
+                           want_recovery_logprobs=False)
+    parity.compare(g, og, inp["uniforms"], inp["draft_len"])

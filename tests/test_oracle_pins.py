@@ -590,6 +590,29 @@ def test_a_uniform_of_one_returns_the_last_token_with_probability(oracle):
         assert r["next_token_logprob"][0] == pytest.approx(np.log(0.5), abs=1e-15)
 
 
+def test_tokens_masked_by_the_generalist_have_no_probability(oracle):
+    """-inf in G: the token has probability zero under P_LLM, so it is rejected when drafted, and the recovery
+    distribution is the softmax of Eq. 8 over the tokens that are left (scipy's softmax treats -inf the same way)."""
+    rng = np.random.default_rng(51)
+    B, K, V = 6, 3, 40
+    G, Sp, Sm, d, u = rand_block(rng, B, K, V)
+    mask = rng.random(G.shape) < 0.3
+    G[mask] = -np.inf
+    u = np.maximum(u, np.float32(1e-3))
+    r = oracle.verify_block(G, Sp, Sm, d, u, lam=0.5, beta=0.8, temperature=0.9)
+    beta, T = float(np.float32(0.8)), float(np.float32(0.9))
+    for b in range(B):
+        n = r["accepted_len"][b]
+        for t in range(min(n + 1, K)):
+            if mask[b, t, d[b, t]]:
+                assert n == t                      # a masked draft token stops the block right there
+        want = log_softmax((G[b, n].astype(np.float64) + beta * (Sp[b, n].astype(np.float64) - Sm[b, n])) / T)
+        got = r["recovery_logprobs"][b]
+        assert np.all(np.isneginf(got[mask[b, n]]))
+        assert np.allclose(got[~mask[b, n]], want[~mask[b, n]], atol=1e-12)
+        assert not mask[b, n, r["next_token"][b]]
+
+
 # ---------------------------------------------------------------- structure of the loop (Algorithm 1)
 
 def test_a_block_equals_its_two_halves_verified_in_turn(oracle):
