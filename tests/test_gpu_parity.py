@@ -863,3 +863,15 @@ def test_tokens_masked_by_the_generalist(binding, oracle, dtype):
     og = parity.oracle_run(oracle, inp, lam=w.lam, beta=w.beta, temperature=w.temperature, greedy=True,
                            want_recovery_logprobs=False)
     parity.compare(g, og, inp["uniforms"], inp["draft_len"])
+
+
+def test_cloud_topk_with_masked_tokens(binding, oracle):
+    w = W.scaled(W.WORKLOADS["c4"], batch=6, vocab=40000, k_max=2, name="topk-masked")
+    inp = W.generate(w, "cuda")
+    mask = torch.rand(inp["G"].shape, device="cuda", generator=torch.Generator("cuda").manual_seed(6)) < 0.5
+    mask[0, :, 40:] = True          # fewer finite logits than the payload holds: the rest of it is -inf entries, lowest ids first
+    inp["G"][mask] = float("-inf")
+    row = torch.tensor([0, 1, 2, 0, 1, 2], dtype=torch.int32, device="cuda")
+    idx, val = binding.cloud_topk(inp["G"], inp["S_noctx"], row, beta=w.beta, topk=32)
+    oidx, oval = oracle.cloud_topk(inp["G"].cpu(), inp["S_noctx"].cpu(), row.cpu(), beta=w.beta, topk=32)
+    assert np.array_equal(idx.cpu().numpy(), oidx) and np.array_equal(val.cpu().numpy(), oval)
