@@ -140,10 +140,12 @@ size_t specsteer_workspace_bytes(const ss_params *params);
  * for some t < K_b -- mark that sequence alone: accepted_len[b] =
  * next_token[b] = -1, next_token_logprob[b] and its draft_logprobs are NaN, its
  * recovery_logprobs row is left unwritten; no out-of-range address is ever
- * formed.  A logit of -inf in G masks that token for the generalist: probability
- * zero, rejected if drafted, never drawn or picked.  Otherwise logits on rows that
- * are read must be finite (behaviour with NaN, +inf, or -inf in S_ctx / S_noctx is
- * unspecified but never faults).
+ * formed.  Masked tokens: a logit of -inf in G gives that token probability zero
+ * (rejected if drafted, never drawn or picked); -inf in BOTH S_ctx and S_noctx at
+ * a token means the specialist has nothing to say about it, and its steering term
+ * in Eq. 8 is taken as 0 (not inf - inf), so a vocabulary mask shared by the three
+ * models is handled.  Anything else non-finite on rows that are read (NaN, +inf,
+ * -inf in only one of the specialist's rows) is unspecified but never faults.
  */
 ss_status specsteer_verify_block(const void *G, const void *S_ctx, const void *S_noctx,
                                  const int32_t *draft, const int32_t *draft_len,

@@ -138,7 +138,8 @@ static void verify_one(const void *G, const void *Sp, const void *Sm, const int3
         const double hl = widen(G, dt, off + v);
         const double hp = widen(Sp, dt, off + v);
         const double hm = widen(Sm, dt, off + v);
-        const double hrec = hl + beta * (hp - hm); /* Eq. 8 */
+        /* Eq. 8.  A token masked (-inf) in both specialist rows carries no steering: 0, not inf - inf. */
+        const double hrec = hl + beta * ((hp == hm) ? 0.0 : hp - hm);
         if (hrec > hmax) { /* strict: the lowest index wins a tie */
             hmax = hrec;
             amax = v;
@@ -304,7 +305,9 @@ int specsteer_oracle_cloud_topk(const void *G, const void *S_noctx, const int32_
         if (row[b] < 0 || row[b] > kmax) continue;
         const int64_t off = (int64_t)b * sb + (int64_t)row[b] * st;
         for (int v = 0; v < V; ++v) {
-            e[v].v = widen(G, dt, off + v) - beta * widen(S_noctx, dt, off + v);
+            const double hl = widen(G, dt, off + v);
+            /* a token the generalist masks (-inf) stays masked whatever the specialist says */
+            e[v].v = (hl == -INFINITY) ? -INFINITY : hl - beta * widen(S_noctx, dt, off + v);
             e[v].idx = v;
         }
         qsort(e, (size_t)V, sizeof(sso_entry), entry_before);

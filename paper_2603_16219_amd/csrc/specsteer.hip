@@ -105,9 +105,14 @@ __device__ __forceinline__ void acc_add_f32(Acc& a, const float (&h)[N], float c
     a.s += t0 + t1;
 }
 
+// The steering difference h_SLM^+ - h_SLM^- of Eq. 8.  A token masked (-inf) in both specialist rows
+// carries no steering -- 0, not inf - inf; for equal finite logits the result is the same 0 as before.
+__device__ __forceinline__ float steer_diff(float sp, float sm) { return sp == sm ? 0.f : sp - sm; }
+__device__ __forceinline__ double steer_diff_d(float sp, float sm) { return sp == sm ? 0.0 : (double)sp - (double)sm; }
+
 // recovery logit in the base-2 exponent domain: y = (G + beta*(S_ctx - S_noctx)) * log2(e)/T, in double.
 __device__ __forceinline__ double rec_y(float g, float sp, float sm, double c, double bc) {
-    return fma((double)g, c, ((double)sp - (double)sm) * bc);
+    return fma((double)g, c, steer_diff_d(sp, sm) * bc);
 }
 
 // Recovery pass accumulate.  The exponent reference is advanced from a cheap fp32 estimate of
@@ -133,7 +138,7 @@ __device__ __forceinline__ void acc_add_rec(Acc& a, const float (&hg)[N], const 
     if (GREEDY) {
 #pragma unroll
         for (int i = 0; i < N; ++i) {
-            const double hr = __dadd_rn((double)hg[i], __dmul_rn(beta, (double)hp[i] - (double)hm[i]));
+            const double hr = __dadd_rn((double)hg[i], __dmul_rn(beta, steer_diff_d(hp[i], hm[i])));
             if (hr > best.v) {
                 best.v = hr;
                 best.idx = first + i;
@@ -144,7 +149,7 @@ __device__ __forceinline__ void acc_add_rec(Acc& a, const float (&hg)[N], const 
     float m = -3.0e38f;
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-        d[i] = hp[i] - hm[i];
+        d[i] = steer_diff(hp[i], hm[i]);
         m = fmaxf(m, fmaf(hg[i], cf, d[i] * bcf));
     }
     // the estimate is within a few 1e-5 of the exact exponent: half a unit of slack keeps z <= ~0.5
@@ -155,7 +160,7 @@ __device__ __forceinline__ void acc_add_rec(Acc& a, const float (&hg)[N], const 
     float t0 = 0.f, t1 = 0.f;
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-        const double dd = (DT == SS_BF16) ? (double)d[i] : ((double)hp[i] - (double)hm[i]);
+        const double dd = (DT == SS_BF16) ? (double)d[i] : steer_diff_d(hp[i], hm[i]);
         const float z = (float)fma((double)hg[i], c, fma(dd, bc, nE));
         if (i & 1) t1 += __builtin_amdgcn_exp2f(z); else t0 += __builtin_amdgcn_exp2f(z);
     }

@@ -35,6 +35,12 @@ constexpr int kTopUnroll = 2;  // vectors per tensor in flight per lane
 constexpr int kEdgeThreads = 256;
 
 // total order of the payload: larger value first, then smaller token id
+// The non-private part of Eq. 8, h_LLM - beta * h_SLM^-, exactly rounded step by step.  A token the
+// generalist masks (-inf) stays at -inf whatever the specialist says (not -inf + inf).
+__device__ __forceinline__ double cloud_logit(float hg, float hm, double beta) {
+    return hg == -__builtin_huge_valf() ? -__builtin_huge_val() : __dsub_rn((double)hg, __dmul_rn(beta, (double)hm));
+}
+
 __device__ __forceinline__ bool beats(double av, int ai, double bv, int bi) {
     return av > bv || (av == bv && ai < bi);
 }
@@ -139,7 +145,7 @@ __device__ void topk_by_insertion(const TopArgs& a, const void* g, const void* s
             bool mine = false;
 #pragma unroll
             for (int i = 0; i < VEC; ++i) {
-                hc[i] = valid[j] ? __dsub_rn((double)hg[i], __dmul_rn(a.beta, (double)hm[i])) : ninf;
+                hc[i] = valid[j] ? cloud_logit(hg[i], hm[i], a.beta) : ninf;
                 mine = mine || (valid[j] && hc[i] >= w.tau_v);  // cheap screen; the exact order is applied below
             }
             const int idx0 = (int)((v0 + j * kStep + lane) * VEC);
@@ -172,7 +178,7 @@ __device__ void topk_by_insertion(const TopArgs& a, const void* g, const void* s
     if (tailc && wave == 0) {  // logits past the last full vector
         const bool valid = lane < tailc;
         const int e = (int)(nvec * VEC) + lane;
-        const double hc = valid ? __dsub_rn((double)ld_elem<DT>(g, e), __dmul_rn(a.beta, (double)ld_elem<DT>(sm, e)))
+        const double hc = valid ? cloud_logit(ld_elem<DT>(g, e), ld_elem<DT>(sm, e), a.beta)
                                 : ninf;
         wave_offer(w, __ballot(valid && beats(hc, e, w.tau_v, w.tau_i)), hc, e, lane, topk);
     }
@@ -369,13 +375,13 @@ __global__ __launch_bounds__(kTopThreads) void cloud_topk_kernel(const TopArgs a
                 unpack(rm[j], hm);
 #pragma unroll
                 for (int i = 0; i < VEC; ++i)
-                    offer(__dsub_rn((double)hg[i], __dmul_rn(a.beta, (double)hm[i])), (int)(v[j] * VEC) + i);
+                    offer(cloud_logit(hg[i], hm[i], a.beta), (int)(v[j] * VEC) + i);
             }
         }
     }
     if (tid < tailc && tmax >= screen) {
         const long e = nvec * VEC + tid;
-        offer(__dsub_rn((double)ld_elem<DT>(g, e), __dmul_rn(a.beta, (double)ld_elem<DT>(sm, e))), (int)e);
+        offer(cloud_logit(ld_elem<DT>(g, e), ld_elem<DT>(sm, e), a.beta), (int)e);
     }
     __syncthreads();
     const int M = cand_count;

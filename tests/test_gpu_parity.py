@@ -875,3 +875,41 @@ def test_cloud_topk_with_masked_tokens(binding, oracle):
     idx, val = binding.cloud_topk(inp["G"], inp["S_noctx"], row, beta=w.beta, topk=32)
     oidx, oval = oracle.cloud_topk(inp["G"].cpu(), inp["S_noctx"].cpu(), row.cpu(), beta=w.beta, topk=32)
     assert np.array_equal(idx.cpu().numpy(), oidx) and np.array_equal(val.cpu().numpy(), oval)
+
+
+@pytest.mark.parametrize("dtype,batch", [("bf16", 24), ("f32", 24), ("bf16", 600)])
+def test_tokens_masked_in_every_model(binding, oracle, dtype, batch):
+    """A vocabulary mask shared by the three models, plus tokens masked for the specialist only (with and without
+    context): no inf - inf anywhere, masked tokens have no probability, the rest of the row is as usual."""
+    import dataclasses
+    w = dataclasses.replace(W.scaled(W.WORKLOADS["c4"], batch=batch, vocab=20000, k_max=5, name=f"mask3-{dtype}-{batch}"),
+                            dtype=dtype)
+    inp = W.generate(w, "cuda")
+    gen = torch.Generator("cuda").manual_seed(8)
+    common = torch.rand(inp["G"].shape, device="cuda", generator=gen) < 0.25
+    common[:, :, 4096:4200] = True
+    spec_only = (torch.rand(inp["G"].shape, device="cuda", generator=gen) < 0.1) & ~common
+    b = torch.arange(w.batch, device="cuda").view(-1, 1).expand(-1, w.k_max)
+    t = torch.arange(w.k_max, device="cuda").view(1, -1).expand(w.batch, -1)
+    common[b, t, inp["draft"].long()] = False        # drafted tokens stay ordinary
+    spec_only[b, t, inp["draft"].long()] = False
+    inp["G"][common] = float("-inf")
+    inp["S_ctx"][common | spec_only] = float("-inf")
+    inp["S_noctx"][common | spec_only] = float("-inf")
+    out, ora, rep = run_both(binding, oracle, w, inp)
+    n, tok = out["accepted_len"].long(), out["next_token"].long()
+    bb = torch.arange(w.batch, device="cuda")
+    assert not common[bb, n, tok].any()
+    lp = out["recovery_logprobs"]
+    assert torch.all(lp[common[bb, n]] == float("-inf")) and torch.all(torch.isfinite(lp[~common[bb, n]]))
+    g = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], lam=w.lam,
+                             beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"], greedy=True)
+    og = parity.oracle_run(oracle, inp, lam=w.lam, beta=w.beta, temperature=w.temperature, greedy=True,
+                           want_recovery_logprobs=False, num_threads=16)
+    parity.compare(g, og, inp["uniforms"], inp["draft_len"])
+    # the deployment split on the same rows
+    row = out["accepted_len"].clamp(min=0)
+    idx, val = binding.cloud_topk(inp["G"], inp["S_noctx"], row, beta=w.beta, topk=32)
+    sel = torch.arange(0, w.batch, max(1, w.batch // 24), device="cuda")
+    oidx, oval = oracle.cloud_topk(inp["G"][sel].cpu(), inp["S_noctx"][sel].cpu(), row[sel].cpu(), beta=w.beta, topk=32)
+    assert np.array_equal(idx[sel].cpu().numpy(), oidx) and np.array_equal(val[sel].cpu().numpy(), oval)

@@ -17,7 +17,7 @@ SOURCE = os.path.join(ROOT, "oracle", "specsteer_oracle.c")
 
 # (what is planted, text in the oracle's source, what replaces its first occurrence)
 MUTANTS = [
-    ("recovery steers away from the context (S_ctx and S_noctx swapped in Eq. 8)", "beta * (hp - hm)", "beta * (hm - hp)"),
+    ("recovery steers away from the context (S_ctx and S_noctx swapped in Eq. 8)", "? 0.0 : hp - hm", "? 0.0 : hm - hp"),
     ("lambda dropped from Eq. 7", "- log(lam))", ")"),
     ("strict acceptance test", "(double)u[t] <= alpha", "(double)u[t] < alpha"),
     ("ratio of Eq. 7 inverted", "lpG - lpS - log(lam)", "lpS - lpG - log(lam)"),
@@ -32,7 +32,9 @@ MUTANTS = [
      "scaled_row(Sm, dt, seq_off + (int64_t)t * st, V, T, sm);\n        const double lpG",
      "scaled_row(Sp, dt, seq_off + (int64_t)t * st, V, T, sm);\n        const double lpG"),
     ("log-sum-exp forgets its maximum", "return m + log(s);", "return log(s);"),
-    ("beta dropped from Eq. 8", "beta * (hp - hm)", "(hp - hm)"),
+    ("beta dropped from Eq. 8", "hl + beta * ((hp", "hl + ((hp"),
+    ("a token masked in both specialist rows poisons the row", "(hp == hm) ? 0.0 : hp - hm", "hp - hm"),
+    ("a token the generalist masks comes back on the cloud side", "(hl == -INFINITY) ? -INFINITY : hl - beta", "hl - beta"),
     ("logits multiplied by T", "widen(base, dtype, off + v) / T", "widen(base, dtype, off + v) * T"),
     ("bf16 widened with the wrong shift", "<< 16", "<< 15"),
     ("uniforms indexed with the draft's row length", "uniforms + (size_t)b * (kmax + 1)", "uniforms + (size_t)b * (kmax)"),
@@ -42,8 +44,8 @@ MUTANTS = [
     ("greedy pick keeps the last maximum", "if (hrec > hmax) {", "if (hrec >= hmax) {"),
     ("greedy pick ignores the steering term", "if (hrec > hmax) {", "if (hl > hmax) {"),
     ("bonus row confused with the last draft row", "int n = K;\n    for (int t = 0; t < K; ++t) {", "int n = K > 0 ? K - 1 : 0;\n    for (int t = 0; t < K; ++t) {"),
-    ("cloud side adds the context-free logits", "widen(G, dt, off + v) - beta * widen(S_noctx, dt, off + v)",
-     "widen(G, dt, off + v) + beta * widen(S_noctx, dt, off + v)"),
+    ("cloud side adds the context-free logits", "hl - beta * widen(S_noctx, dt, off + v)",
+     "hl + beta * widen(S_noctx, dt, off + v)"),
     ("payload ties broken by the higher id", "return (a->idx > b->idx) - (a->idx < b->idx);",
      "return (a->idx < b->idx) - (a->idx > b->idx);"),
     ("payload in increasing order", "if (a->v > b->v) return -1;\n    if (a->v < b->v) return 1;",

@@ -613,6 +613,60 @@ def test_tokens_masked_by_the_generalist_have_no_probability(oracle):
         assert not mask[b, n, r["next_token"][b]]
 
 
+def test_tokens_masked_in_every_model(oracle):
+    """A vocabulary mask shared by the three models (-inf in G, S_ctx and S_noctx at the same ids): those tokens
+    have no probability anywhere, the rest of the row is untouched -- the steering term of a masked token is
+    nothing, not inf - inf.  A token masked for the specialist only (with and without context) keeps the
+    generalist's logit."""
+    rng = np.random.default_rng(52)
+    B, K, V = 5, 2, 30
+    G, Sp, Sm, d, u = rand_block(rng, B, K, V)
+    common = rng.random((B, K + 1, V)) < 0.25
+    spec_only = (rng.random((B, K + 1, V)) < 0.15) & ~common
+    for b in range(B):
+        for t in range(K):
+            common[b, t, d[b, t]] = spec_only[b, t, d[b, t]] = False   # the drafted tokens stay ordinary
+    G[common] = -np.inf
+    Sp[common | spec_only] = -np.inf
+    Sm[common | spec_only] = -np.inf
+    r = oracle.verify_block(G, Sp, Sm, d, u, lam=0.5, beta=1.3, temperature=0.8)
+    beta, T = float(np.float32(1.3)), float(np.float32(0.8))
+    for b in range(B):
+        n = r["accepted_len"][b]
+        hl, hp, hm = (x[b, n].astype(np.float64) for x in (G, Sp, Sm))
+        steer = np.where(np.isneginf(hp) & np.isneginf(hm), 0.0, np.where(np.isneginf(hp), 0.0, hp) - np.where(np.isneginf(hm), 0.0, hm))
+        want = log_softmax((hl + beta * steer) / T)
+        got = r["recovery_logprobs"][b]
+        assert np.all(np.isneginf(got[common[b, n]])) and np.all(np.isfinite(got[~common[b, n]]))
+        assert np.allclose(got[~common[b, n]], want[~common[b, n]], atol=1e-12)
+        assert np.isclose(np.exp(got).sum(), 1.0, atol=1e-12)
+    # greedy: never a masked token, and a specialist-only mask leaves the generalist's logit in the race
+    g = oracle.verify_block(G, Sp, Sm, d, u, lam=0.5, beta=1.3, temperature=0.8, greedy=True)
+    for b in range(B):
+        n = g["accepted_len"][b]
+        assert g["next_token"][b] == int(np.argmax(g["recovery_logprobs"][b])) and not common[b, n, g["next_token"][b]]
+
+
+def test_cloud_topk_keeps_masked_tokens_masked(oracle):
+    rng = np.random.default_rng(53)
+    V, k = 40, 8
+    G, _, Sm, _, _ = rand_block(rng, 2, 0, V)
+    masked = np.zeros(V, bool)
+    masked[[1, 5, 6, 30]] = True
+    G[0, 0, masked] = -np.inf
+    Sm[0, 0, masked] = -np.inf         # -inf - beta * (-inf) must not come back as a candidate
+    G[1, 0, 6:] = -np.inf              # second row: fewer finite logits than payload slots
+    Sm[1, 0, 6:] = -np.inf
+    row = np.zeros(2, np.int32)
+    idx, val = oracle.cloud_topk(G, Sm, row, beta=0.9, topk=k)
+    h0 = G[0, 0].astype(np.float64) - float(np.float32(0.9)) * np.where(masked, 0.0, Sm[0, 0].astype(np.float64))
+    want0 = np.lexsort((np.arange(V), -h0))[:k]
+    assert idx[0].tolist() == want0.tolist() and not masked[idx[0]].any()
+    assert np.array_equal(val[0], h0[want0].astype(np.float32))
+    assert sorted(idx[1, :6].tolist()) == [0, 1, 2, 3, 4, 5] and idx[1, 6:].tolist() == [6, 7]
+    assert np.all(np.isneginf(val[1, 6:]))
+
+
 # ---------------------------------------------------------------- structure of the loop (Algorithm 1)
 
 def test_a_block_equals_its_two_halves_verified_in_turn(oracle):
