@@ -619,17 +619,19 @@ __device__ __forceinline__ const Partial* partials_of(const RecArgs& a, int b, i
     return a.partial2 + (r * 2 + x) * a.NS2;
 }
 
-// Phase 2 for one sequence by its workgroup of NT threads, on positions [0, Kt):
+// Phase 2 for one sequence by its workgroup of NT threads, on positions [T0, Kt) (those before T0
+// are known to have been accepted):
 //   2a  every (position, tensor) pair gets a wave: merge its slice partials, gather the draft
 //       token's logit, leave log P(y_t) in lp[2t + x]        (two memory round trips in all)
 //   2b  wave 0: Eq. 7 on every position, first rejection by ballot -> *sh_n (Kt if none)
 // A draft id outside the vocabulary among those positions sets *sh_bad.  Ends with a barrier.
 template <int DT, int NT>
-__device__ __forceinline__ void ratio_test_block(const RecArgs& a, int b, int Kt, double* lp, int* sh_n, int* sh_bad) {
+__device__ __forceinline__ void ratio_test_block(const RecArgs& a, int b, int T0, int Kt, double* lp, int* sh_n,
+                                                 int* sh_bad) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     constexpr int NW = NT / kWave;
     const int kmax = a.kmax, V = a.V;
-    for (int q = wave; q < 2 * Kt; q += NW) {
+    for (int q = 2 * T0 + wave; q < 2 * Kt; q += NW) {
         const int t = q >> 1, x = q & 1;
         const int y = a.draft[(long)b * kmax + t];  // wave-uniform
         const bool ok = (y >= 0 && y < V);
@@ -644,7 +646,7 @@ __device__ __forceinline__ void ratio_test_block(const RecArgs& a, int b, int Kt
     __syncthreads();
     if (wave == 0) {
         int first_rej = Kt;
-        for (int t0 = 0; t0 < Kt; t0 += kWave) {
+        for (int t0 = T0; t0 < Kt; t0 += kWave) {
             const int t = t0 + lane;
             bool rej = false;
             if (t < Kt) {
@@ -689,7 +691,7 @@ __global__ __launch_bounds__(kRecThreads) void verdict_kernel(const RecArgs a, i
     }
     __syncthreads();
     const int Kt = sh_bad ? 0 : min(K, a.t1);
-    ratio_test_block<DT, kRecThreads>(a, b, Kt, smem_d, &sh_n, &sh_bad);
+    ratio_test_block<DT, kRecThreads>(a, b, 0, Kt, smem_d, &sh_n, &sh_bad);
     if (tid == 0) {
         const bool bad = sh_bad != 0;
         alive[b] = (!bad && sh_n == Kt && K > a.t1) ? 1 : 0;
@@ -746,16 +748,17 @@ __global__ __launch_bounds__(NT) void accept_recover_kernel(const RecArgs a) {
     const int K = a.draft_len ? a.draft_len[b] : kmax;
     const bool bad_len = (K < 0 || K > kmax) || (a.flagged && a.flagged[b]);
     // Two-pass schedule: a sequence the verdict kernel saw rejected inside the first window keeps
-    // that first-rejection index (its later rows were never scored); every other sequence has all
-    // of its rows and is tested here over all K positions.
-    const bool settled = a.alive && !a.alive[b] && !bad_len && K > a.t1;
+    // that first-rejection index (its later rows were never scored); a sequence still in play after
+    // that window is tested here on its remaining positions, any other over all K positions.
+    const bool in_play = a.alive && a.alive[b] && !bad_len;
+    const bool settled = a.alive && !in_play && !bad_len && K > a.t1;
     const int Kt = bad_len ? 0 : K;
     if (tid == 0) {
         sh_bad = bad_len ? 1 : 0;
         sh_n = settled ? a.first_rej[b] : 0;
     }
     __syncthreads();
-    if (!settled) ratio_test_block<DT, NT>(a, b, Kt, lp, &sh_n, &sh_bad);
+    if (!settled) ratio_test_block<DT, NT>(a, b, in_play ? a.t1 : 0, Kt, lp, &sh_n, &sh_bad);
     const bool bad = sh_bad != 0;
     if (a.draft_logprobs && part == 0) {  // valid positions from LDS, padded slots 0, a flagged sequence NaN throughout
         const float nanv = __int_as_float(0x7FC00000);
