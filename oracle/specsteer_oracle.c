@@ -85,12 +85,12 @@ static double log_sum_exp(const double *x, int V) {
 }
 
 /*
- * One sequence.  Scratch rows g, sp, sm hold V doubles each.
+ * One sequence.  Scratch rows g and sm hold V doubles each.
  * Returns through the out pointers for this sequence only (already offset).
  */
 static void verify_one(const void *G, const void *Sp, const void *Sm, const int32_t *draft, int K,
                        const float *u, const sso_params *p, int64_t seq_off, int64_t st, double *g,
-                       double *sp, double *sm, int32_t *accepted_len, int32_t *next_token,
+                       double *sm, int32_t *accepted_len, int32_t *next_token,
                        double *next_token_logprob, double *recovery_logprobs, double *draft_logprobs,
                        double *alpha_out, double *sample_margin) {
     const int V = p->vocab, kmax = p->k_max, dt = p->dtype;
@@ -211,7 +211,6 @@ int specsteer_oracle_verify_block(const void *G, const void *S_ctx, const void *
 #pragma omp parallel num_threads(nthreads)
     {
         double *g = (double *)malloc((size_t)V * sizeof(double));
-        double *sp = (double *)malloc((size_t)V * sizeof(double));
         double *sm = (double *)malloc((size_t)V * sizeof(double));
 #pragma omp for schedule(dynamic, 1)
         for (int b = 0; b < B; ++b) {
@@ -235,14 +234,13 @@ int specsteer_oracle_verify_block(const void *G, const void *S_ctx, const void *
                 continue;
             }
             verify_one(G, S_ctx, S_noctx, draft + (size_t)b * kmax, K,
-                       uniforms + (size_t)b * (kmax + 1), p, (int64_t)b * sb, st, g, sp, sm,
+                       uniforms + (size_t)b * (kmax + 1), p, (int64_t)b * sb, st, g, sm,
                        accepted_len + b, next_token + b,
                        next_token_logprob ? next_token_logprob + b : NULL,
                        recovery_logprobs ? recovery_logprobs + (size_t)b * V : NULL, dl, al,
                        sample_margin ? sample_margin + b : NULL);
         }
         free(g);
-        free(sp);
         free(sm);
     }
     return 0;
