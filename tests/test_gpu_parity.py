@@ -913,3 +913,35 @@ def test_tokens_masked_in_every_model(binding, oracle, dtype, batch):
     sel = torch.arange(0, w.batch, max(1, w.batch // 24), device="cuda")
     oidx, oval = oracle.cloud_topk(inp["G"][sel].cpu(), inp["S_noctx"][sel].cpu(), row[sel].cpu(), beta=w.beta, topk=32)
     assert np.array_equal(idx[sel].cpu().numpy(), oidx) and np.array_equal(val[sel].cpu().numpy(), oval)
+
+
+def test_gpu_against_the_frozen_oracle_block(binding):
+    """The stored expected values were written by tests/golden/make_oracle_fixture.py, which calls only the oracle."""
+    import importlib.util
+    import json
+    import os
+
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_oracle_fixture", os.path.join(here, "golden", "make_oracle_fixture.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    want = json.load(open(os.path.join(here, "golden", "oracle_block_fixture.json")))["outputs"]
+    G, Sp, Sm, draft, draft_len, u = mod.build_inputs()
+    dev = "cuda"
+    t = lambda a, dt=None: torch.from_numpy(np.ascontiguousarray(a)).to(dev) if dt is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev).to(dt)
+    for dtype, tdt in (("f32", torch.float32), ("bf16", torch.bfloat16)):
+        for greedy in (False, True):
+            w = want[f"{dtype}{'-greedy' if greedy else ''}"]
+            out = binding.verify_block(t(G, tdt), t(Sp, tdt), t(Sm, tdt), t(draft), t(u), lam=0.5, beta=0.75,
+                                       temperature=0.8, draft_len=t(draft_len), greedy=greedy)
+            assert out["accepted_len"].cpu().tolist() == w["accepted_len"]
+            assert out["next_token"].cpu().tolist() == w["next_token"]
+            for got, exp in zip(out["next_token_logprob"].cpu().tolist(), w["next_token_logprob"]):
+                assert (exp is None and got != got) or abs(got - exp) <= 1e-5
+    s = want["split"]
+    idx, val = binding.cloud_topk(t(G), t(Sm), t(np.array(s["row"], np.int32)), beta=0.75, topk=4)
+    assert idx.cpu().tolist() == s["index"]
+    assert np.array_equal(val.cpu().numpy(), np.array(s["value"], np.float32))
+    e = binding.edge_resample(idx, val, t(Sp), t(np.array(s["row"], np.int32)), t(u[:, -1].copy()), beta=0.75, temperature=0.8)
+    assert e["next_token"].cpu().tolist() == s["next_token"]
+    assert np.allclose(e["next_token_logprob"].cpu().numpy(), np.array(s["next_token_logprob"]), atol=1e-5)

@@ -705,3 +705,29 @@ def test_sequences_do_not_interact(oracle):
     got = oracle.verify_block(G[perm], Sp[perm], Sm[perm], d[perm], u[perm], draft_len=dl[perm], beta=1.4)
     for k in ("accepted_len", "next_token", "next_token_logprob", "recovery_logprobs"):
         assert np.array_equal(ref[k][perm], got[k]), k
+
+
+# ---------------------------------------------------------------- frozen outputs
+
+def test_oracle_reproduces_its_frozen_block():
+    """tests/golden/oracle_block_fixture.json was written by tests/golden/make_oracle_fixture.py (numpy + oracle
+    only).  It pins nothing to the paper by itself; it makes any later drift of the oracle's arithmetic visible."""
+    import importlib.util
+
+    spec = importlib.util.spec_from_file_location("make_oracle_fixture", os.path.join(HERE, "golden", "make_oracle_fixture.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    want = json.load(open(os.path.join(HERE, "golden", "oracle_block_fixture.json")))["outputs"]
+    got = mod.run_all(*mod.build_inputs())
+    assert got.keys() == want.keys()
+
+    def same(a, b):
+        if isinstance(a, list):
+            return len(a) == len(b) and all(same(x, y) for x, y in zip(a, b))
+        if isinstance(a, float) and isinstance(b, float):
+            return a == b or abs(a - b) <= 1e-14 * max(1.0, abs(b))
+        return a == b
+
+    for case in want:
+        for key in want[case]:
+            assert same(got[case][key], want[case][key]), (case, key)
