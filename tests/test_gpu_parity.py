@@ -945,3 +945,26 @@ def test_gpu_against_the_frozen_oracle_block(binding):
     e = binding.edge_resample(idx, val, t(Sp), t(np.array(s["row"], np.int32)), t(u[:, -1].copy()), beta=0.75, temperature=0.8)
     assert e["next_token"].cpu().tolist() == s["next_token"]
     assert np.allclose(e["next_token_logprob"].cpu().numpy(), np.array(s["next_token_logprob"]), atol=1e-5)
+
+
+@pytest.mark.parametrize("name,batch", [("c2", 8), ("c4", 160)])
+def test_timed_entry_point_gives_the_same_outputs_and_sane_times(binding, name, batch):
+    """specsteer_verify_block_timed is the same operation bracketed with events: identical outputs, one
+    non-negative time per stage, stages that do not run report (close to) nothing."""
+    w = W.scaled(W.WORKLOADS[name], batch=batch, name=f"timed-{name}")
+    inp = W.generate(w, "cuda")
+    p = binding.make_params(w.batch, w.k_max, w.vocab, W.torch_dtype(w.dtype), lam=w.lam, beta=w.beta,
+                            temperature=w.temperature)
+    ws = torch.empty(binding.workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    mk = lambda dt: torch.empty(w.batch, dtype=dt, device="cuda")
+    a1, t1, l1, a2, t2, l2 = mk(torch.int32), mk(torch.int32), mk(torch.float32), mk(torch.int32), mk(torch.int32), mk(torch.float32)
+    args = (inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["draft_len"], inp["uniforms"], p)
+    binding.verify_block_raw(*args, a1, t1, l1, None, None, ws)
+    ms = binding.verify_block_raw(*args, a2, t2, l2, None, None, ws, timed=True)
+    torch.cuda.synchronize()
+    assert torch.equal(a1, a2) and torch.equal(t1, t2) and torch.equal(l1, l2)
+    assert set(ms) == set(binding.STAGES) and all(0.0 <= v < 50.0 for v in ms.values())
+    two_pass = binding.first_window(p) < w.k_max
+    assert ms["row_pass1"] > 0 and ms["recover"] > 0
+    if not two_pass:
+        assert ms["verdict"] < 0.02 and ms["row_pass2"] < 0.02
