@@ -968,3 +968,44 @@ def test_timed_entry_point_gives_the_same_outputs_and_sane_times(binding, name, 
     assert ms["row_pass1"] > 0 and ms["recover"] > 0
     if not two_pass:
         assert ms["verdict"] < 0.02 and ms["row_pass2"] < 0.02
+
+
+def test_concurrent_calls_from_several_threads_and_streams(binding):
+    """The header promises re-entrancy across streams given distinct workspaces: four host threads, each on its
+    own stream with its own workspace and outputs, repeatedly verify different blocks at once; every result must
+    be what the same block gives when verified alone."""
+    import threading
+
+    w = W.scaled(W.WORKLOADS["c4"], batch=40, vocab=60000, k_max=8, name="threads")
+    jobs = []
+    for i in range(4):
+        inp = W.generate(w, "cuda", seed_shift=i)
+        ref = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], lam=w.lam,
+                                   beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"])
+        jobs.append((inp, ref))
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(i):
+        try:
+            inp, ref = jobs[i]
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                for _ in range(25):
+                    out = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"],
+                                               lam=w.lam, beta=w.beta, temperature=w.temperature,
+                                               draft_len=inp["draft_len"])
+                    stream.synchronize()
+                    for k in ("accepted_len", "next_token", "next_token_logprob"):
+                        if not torch.equal(out[k], ref[k]):
+                            errors.append((i, k))
+        except Exception as e:  # surfaced in the main thread below
+            errors.append((i, repr(e)))
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    assert not any(t.is_alive() for t in threads)
+    assert not errors, errors[:5]
