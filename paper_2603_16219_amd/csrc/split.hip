@@ -11,7 +11,7 @@
 //                 and remembering only per-lane group maxima; those give a lower bound on the
 //                 k-th largest logit without any cross-lane work in the stream, and only the few
 //                 vectors that reach the bound are read again and evaluated exactly in double.
-//                 The survivors (100-200 of 128 K) rank themselves in LDS.  A row degenerate enough
+//                 The survivors (100-200 of 128 K) are ranked by the 16 waves together.  A row degenerate enough
 //                 to overflow the survivor buffer falls back to an exact insertion-based path.
 //   edge_resample one wave per sequence: lane j owns payload entry j, gathers h_SLM^+ at its
 //                 token, and the softmax over the k candidates, the inverse-CDF scan and the
@@ -34,13 +34,13 @@ constexpr int kTopWaves = kTopThreads / kWave;
 constexpr int kTopUnroll = 2;  // vectors per tensor in flight per lane
 constexpr int kEdgeThreads = 256;
 
-// total order of the payload: larger value first, then smaller token id
 // The non-private part of Eq. 8, h_LLM - beta * h_SLM^-, exactly rounded step by step.  A token the
 // generalist masks (-inf) stays at -inf whatever the specialist says (not -inf + inf).
 __device__ __forceinline__ double cloud_logit(float hg, float hm, double beta) {
     return hg == -__builtin_huge_valf() ? -__builtin_huge_val() : __dsub_rn((double)hg, __dmul_rn(beta, (double)hm));
 }
 
+// total order of the payload: larger value first, then smaller token id
 __device__ __forceinline__ bool beats(double av, int ai, double bv, int bi) {
     return av > bv || (av == bv && ai < bi);
 }
