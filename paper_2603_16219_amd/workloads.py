@@ -113,7 +113,9 @@ def generate(w: Workload, device="cpu", seed_shift: int = 0, seq_chunk: int = 4)
             del rows, cdf
     uniforms = torch.rand(B, K1, generator=g_unif, device=dev, dtype=torch.float32)
     draft_len = None
-    if w.ragged:
+    if w.ragged and w.k_max == 0:
+        draft_len = torch.zeros(B, dtype=torch.int32, device=dev)
+    elif w.ragged:
         draft_len = torch.randint(1, w.k_max + 1, (B,), generator=gen(_SEED_LEN), device=dev,
                                   dtype=torch.int32)
     return {"G": G, "S_ctx": Sp, "S_noctx": Sm, "draft": draft, "draft_len": draft_len,

@@ -1009,3 +1009,45 @@ def test_concurrent_calls_from_several_threads_and_streams(binding):
         t.join(timeout=100)
     assert not any(t.is_alive() for t in threads)
     assert not errors, errors[:5]
+
+
+# ------------------------------------------------------------------ random configurations
+
+def random_case(seed):
+    """One seeded configuration inside the documented limits: shapes, dtype, hyper-parameters, raggedness,
+    row padding, decoding mode and requested outputs all drawn at random."""
+    import dataclasses
+    rng = np.random.default_rng(1000 + seed)
+    B = int(rng.choice([1, 2, 3, 5, 8, 17, 33, 64, 100, 129, 200, 300, 520]))
+    K = int(rng.choice([0, 1, 2, 3, 4, 5, 8, 13, 16, 20]))
+    V = int(rng.choice([1, 7, 64, 777, 2048, 4099, 20000, 32776, 50001, 70000]))
+    while B * (K + 1) * V > 120_000_000:       # keep the oracle's share of the test short
+        B = max(1, B // 2)
+    pad = int(rng.choice([0, 0, 8 - V % 8 if V % 8 else 8, 3]))
+    w = dataclasses.replace(
+        W.scaled(W.WORKLOADS[str(rng.choice(["c2", "c3", "c4", "c5"]))], batch=B, vocab=V + pad, k_max=K, name=f"rand{seed}"),
+        dtype=str(rng.choice(["bf16", "f32"])), beta=float(rng.choice([0.0, 0.5, 1.0, 1.5, -0.5])),
+        lam=float(rng.choice([0.5, 1.0, 0.1, 2.0])), temperature=float(rng.choice([1.0, 0.7, 1.6, 0.2])))
+    return w, V, pad, bool(rng.integers(2)), bool(rng.integers(2)), bool(rng.integers(2)), rng
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_configurations(binding, oracle, seed):
+    import dataclasses
+    w, V, pad, greedy, want_rec, want_dlp, rng = random_case(seed)
+    inp = W.generate(w, "cuda")
+    if pad:
+        for k in ("G", "S_ctx", "S_noctx"):
+            inp[k][..., V:] = float("nan")
+            inp[k] = inp[k][..., :V]
+        inp["draft"] = inp["draft"].clamp(max=V - 1)
+    if inp["draft_len"] is None and w.k_max > 0 and rng.integers(2):
+        inp["draft_len"] = torch.from_numpy(rng.integers(0, w.k_max + 1, w.batch).astype(np.int32)).cuda()
+    w = dataclasses.replace(w, vocab=V)
+    out = binding.verify_block(inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["uniforms"], lam=w.lam,
+                               beta=w.beta, temperature=w.temperature, draft_len=inp["draft_len"], greedy=greedy,
+                               want_recovery_logprobs=want_rec, want_draft_logprobs=want_dlp)
+    ora = parity.oracle_run(oracle, inp, lam=w.lam, beta=w.beta, temperature=w.temperature, greedy=greedy,
+                            want_recovery_logprobs=want_rec, num_threads=16)
+    rep = parity.compare(out, ora, inp["uniforms"], inp["draft_len"])
+    assert rep["unexcused_mismatches"] == 0
