@@ -49,7 +49,7 @@ typedef enum {
     SS_ERR_SHAPE = 2,     /* batch < 0, k_max < 0, vocab < 1 or above the limits      */
     SS_ERR_DTYPE = 3,     /* dtype is not an ss_dtype                                 */
     SS_ERR_PARAM = 4,     /* lambda, beta, temperature or flags out of range          */
-    SS_ERR_STRIDE = 5,    /* strides overlap rows or are negative                     */
+    SS_ERR_STRIDE = 5,    /* strides overlap rows or are negative, or a logit pointer is off its element size */
     SS_ERR_WORKSPACE = 6, /* workspace NULL, misaligned or smaller than required      */
     SS_ERR_DEVICE = 7     /* a HIP call failed (launch error); see hipGetLastError    */
 } ss_status;
@@ -110,10 +110,11 @@ size_t specsteer_workspace_bytes(const ss_params *params);
  * The block (Algorithm 1 phases 2-3, Eq. 7, Eq. 8; see the top of this file).
  *
  *   G, S_ctx, S_noctx  device, [B, k_max+1, V] logits of params->dtype.  With beta == 0 the
- *                      recovery distribution is Softmax(G/T) and S_ctx is not read.  The fast
- *                      path needs all three base pointers 16-byte aligned and both
- *                      strides multiples of 16 bytes; anything else (any V, any
- *                      element-aligned pointer) takes a slower element-wise path.
+ *                      recovery distribution is Softmax(G/T) and S_ctx is not read.  Pointers
+ *                      need element alignment only (SS_ERR_STRIDE otherwise) and any V works;
+ *                      rows that start on 16-byte boundaries (base pointers 16-byte aligned,
+ *                      strides multiples of 16 bytes) stream fastest, others cost about a
+ *                      third more.
  *   draft              device, [B, k_max] int32 token ids; slots t >= K_b ignored.
  *                      May be NULL when k_max == 0.
  *   draft_len          device, [B] int32 K_b, or NULL meaning K_b = k_max for all b.

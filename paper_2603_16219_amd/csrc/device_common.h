@@ -102,14 +102,15 @@ __device__ __forceinline__ int first_lane(unsigned long long mask) { return __ff
 template <int DT, int VEC> struct RawT;
 template <> struct RawT<SS_BF16, 8> { using type = uint4; };
 template <> struct RawT<SS_F32, 4> { using type = float4; };
-template <> struct RawT<SS_BF16, 1> { using type = unsigned short; };
-template <> struct RawT<SS_F32, 1> { using type = float; };
 
 // Logit rows are streamed once and never reused by the same kernel: non-temporal loads keep
 // them from displacing each other in L2 / Infinity Cache and measure ~12 % faster than plain
 // loads on a pure read of this size.
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
+// The vector types only promise element alignment (2 bytes for bf16, 4 for fp32): gfx950 under ROCm runs
+// with unaligned access enabled, so the same 16-byte load instruction serves rows that start anywhere
+// (an odd vocabulary size with dense rows) at the cost of an extra cache line per wave-load.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4), aligned(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4), aligned(4)));
 
 template <int DT, int VEC>
 __device__ __forceinline__ typename RawT<DT, VEC>::type ld_raw(const void* row, long vec);
@@ -122,14 +123,6 @@ template <>
 __device__ __forceinline__ float4 ld_raw<SS_F32, 4>(const void* row, long vec) {
     const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(row) + vec);
     return make_float4(t.x, t.y, t.z, t.w);
-}
-template <>
-__device__ __forceinline__ unsigned short ld_raw<SS_BF16, 1>(const void* row, long vec) {
-    return __builtin_nontemporal_load(reinterpret_cast<const unsigned short*>(row) + vec);
-}
-template <>
-__device__ __forceinline__ float ld_raw<SS_F32, 1>(const void* row, long vec) {
-    return __builtin_nontemporal_load(reinterpret_cast<const float*>(row) + vec);
 }
 
 __device__ __forceinline__ float bf16_lo(unsigned w) { return __uint_as_float(w << 16); }
@@ -144,8 +137,6 @@ __device__ __forceinline__ void unpack(const uint4& r, float (&h)[8]) {
 __device__ __forceinline__ void unpack(const float4& r, float (&h)[4]) {
     h[0] = r.x; h[1] = r.y; h[2] = r.z; h[3] = r.w;
 }
-__device__ __forceinline__ void unpack(unsigned short r, float (&h)[1]) { h[0] = __uint_as_float((unsigned)r << 16); }
-__device__ __forceinline__ void unpack(float r, float (&h)[1]) { h[0] = r; }
 
 template <int DT>
 __device__ __forceinline__ float ld_elem(const void* row, long e) {

@@ -241,7 +241,7 @@ struct LseArgs {
     Partial* partial;          // [rows][2][NS]
     long sb, st;               // element strides
     int B, kmax, V, NS;
-    int slice_vecs;            // vectors (of the fast path's width) per slice
+    int slice_vecs;            // 16-byte vectors per slice
     int list_in_lds;           // build the row list in LDS (else row_off was filled by prep_rows)
     float c_hi;                // fl32(log2(e)/T)
     uint32_t* zero_ptr;        // arrival counters of a split recovery: workgroup 0 clears zero_n of them
@@ -253,7 +253,7 @@ struct LseArgs {
 // strides over the item list.  Ragged batches build the row list in LDS at kernel start
 // (every workgroup repeats the same small scan), so no separate launch is needed.
 // Workgroup 0 also publishes the row list for the kernels that consume the partials.
-template <int DT, int VEC, int VECFAST, int kUnroll>
+template <int DT, int VEC, int kUnroll>
 __global__ __launch_bounds__(kLseThreads) void row_lse_kernel(const LseArgs a) {
     extern __shared__ int lds_off[];
     const int lane = threadIdx.x & 63;
@@ -271,8 +271,7 @@ __global__ __launch_bounds__(kLseThreads) void row_lse_kernel(const LseArgs a) {
         for (int i = threadIdx.x; i < a.zero_n; i += kLseThreads) a.zero_ptr[i] = 0u;
     const int R = ragged ? off[a.B] : a.B * a.uniform_rows;
     const long items = (long)R * 2 * a.NS;
-    // a slice is slice_vecs vectors of the fast width; the element-wise path covers the same logits
-    const long slice_units = (long)a.slice_vecs * (VECFAST / VEC);
+    const long slice_units = a.slice_vecs;
     const long nvec = a.V / VEC;
     const int tailc = a.V - (int)(nvec * VEC);
     constexpr long kGroup = (long)kWave * kUnroll;
@@ -872,7 +871,7 @@ __global__ void zero_u32_kernel(uint32_t* p, int n) {
 // ------------------------------------------------------------------ host side
 
 struct Plan {
-    int vecfast;     // logits per 16-byte vector
+    int vec;         // logits per 16-byte vector
     int NS, slice_vecs;    // first row pass: slices per row, fast-width vectors per slice
     int NS2, slice_vecs2;  // second row pass
     int NSf, slice_vecsf;  // one pass over all k_max positions (taken when draft_logprobs is requested)
@@ -947,8 +946,8 @@ void slice_plan(long nvec, long row_tensors, int& NS, int& slice_vecs) {
 
 Plan make_plan(const ss_params* p) {
     Plan pl;
-    pl.vecfast = p->dtype == SS_BF16 ? 8 : 4;
-    const long nvec = (p->vocab + pl.vecfast - 1) / pl.vecfast;
+    pl.vec = p->dtype == SS_BF16 ? 8 : 4;
+    const long nvec = (p->vocab + pl.vec - 1) / pl.vec;
     pl.t1 = first_window(p);
     const long rows1 = (long)p->batch * pl.t1, rows2 = (long)p->batch * (p->k_max - pl.t1);
     slice_plan(nvec, rows1 * 2, pl.NS, pl.slice_vecs);
@@ -971,16 +970,14 @@ Plan make_plan(const ss_params* p) {
     if (p->batch >= 1 && p->batch <= kSplitMaxBatch) {
         pl.off_arrive = o;     o += align_up(B * sizeof(uint32_t), 256);
         pl.off_part_best = o;  o += align_up(B * kSplitMaxParts * sizeof(Best), 256);
-        // sized for whichever path has more chunks (normally the element-wise one, whose chunks are smaller)
-        const int nc1 = chunks_per_row(p->vocab, 1), ncf = chunks_per_row(p->vocab, pl.vecfast);
-        pl.off_chunk_tab = o;  o += align_up(B * (size_t)(nc1 > ncf ? nc1 : ncf) * sizeof(Partial), 256);
+        pl.off_chunk_tab = o;  o += align_up(B * (size_t)chunks_per_row(p->vocab, pl.vec) * sizeof(Partial), 256);
     }
     pl.bytes = o;
     return pl;
 }
 
 // One row pass over window `win`.  `uniform_rows` > 0 when every sequence has that many rows.
-template <int DT, int VEC, int VECFAST>
+template <int DT, int VEC>
 void launch_row_pass(LseArgs la, const RowWindow& win, int uniform_rows, int32_t* row_off, Partial* partial,
                      long max_rows, hipStream_t stream) {
     const int B = la.B;
@@ -1001,11 +998,11 @@ void launch_row_pass(LseArgs la, const RowWindow& win, int uniform_rows, int32_t
     const long cap = (long)cus * kLseWgPerCu;
     if (wgs > cap) wgs = cap;
     const size_t lds = la.list_in_lds ? (size_t)(B + 1) * sizeof(int) : 0;
-    hipLaunchKernelGGL((row_lse_kernel<DT, VEC, VECFAST, kLseUnroll>), dim3((unsigned)wgs), dim3(kLseThreads), lds,
+    hipLaunchKernelGGL((row_lse_kernel<DT, VEC, kLseUnroll>), dim3((unsigned)wgs), dim3(kLseThreads), lds,
                        stream, la);
 }
 
-template <int DT, int VEC, int VECFAST>
+template <int DT, int VEC>
 hipError_t launch_all(LseArgs la, RecArgs ra, const Plan& pl, char* ws, hipStream_t stream, hipEvent_t* ev) {
     const int B = ra.B, kmax = ra.kmax, V = ra.V;
     int32_t* off1 = reinterpret_cast<int32_t*>(ws);
@@ -1053,7 +1050,7 @@ hipError_t launch_all(LseArgs la, RecArgs ra, const Plan& pl, char* ws, hipStrea
     if (kmax == 0 && split)  // no row pass to clear the arrival counters
         hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(kSplitMaxBatch), 0, stream, ra.arrive, B);
     if (kmax > 0)
-        launch_row_pass<DT, VEC, VECFAST>(la, RowWindow{ragged ? ra.draft_len : nullptr, nullptr, kmax, 0, t1},
+        launch_row_pass<DT, VEC>(la, RowWindow{ragged ? ra.draft_len : nullptr, nullptr, kmax, 0, t1},
                                           ragged ? 0 : t1, off1, partial1, (long)B * t1, stream);
     mark(1);
     if (two_pass)
@@ -1064,7 +1061,7 @@ hipError_t launch_all(LseArgs la, RecArgs ra, const Plan& pl, char* ws, hipStrea
         la.NS = pl.NS2;
         la.slice_vecs = pl.slice_vecs2;
         la.zero_n = 0;
-        launch_row_pass<DT, VEC, VECFAST>(la, RowWindow{ra.draft_len, alive, kmax, t1, kmax}, 0, off2, partial2,
+        launch_row_pass<DT, VEC>(la, RowWindow{ra.draft_len, alive, kmax, t1, kmax}, 0, off2, partial2,
                                           (long)B * (kmax - t1), stream);
     }
     mark(3);
@@ -1112,15 +1109,16 @@ ss_status verify_block_impl(const void* G, const void* S_ctx, const void* S_noct
     const long st = params->stride_t ? params->stride_t : V;
     const long sb = params->stride_b ? params->stride_b : (long)(params->k_max + 1) * st;
     if (st < V || sb < (long)params->k_max * st + V) return SS_ERR_STRIDE;
+    // logits must sit on element boundaries; the 16-byte loads themselves need no more than that
+    const uintptr_t esz = params->dtype == SS_BF16 ? 2 : 4;
+    if (((reinterpret_cast<uintptr_t>(G) | reinterpret_cast<uintptr_t>(S_ctx) | reinterpret_cast<uintptr_t>(S_noctx)) &
+         (esz - 1)) != 0)
+        return SS_ERR_STRIDE;
     const Plan pl = make_plan(params);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 || workspace_bytes < pl.bytes)
         return SS_ERR_WORKSPACE;
     if (params->batch == 0) return SS_OK;
 
-    const int esz = params->dtype == SS_BF16 ? 2 : 4;
-    const bool fast = ((reinterpret_cast<uintptr_t>(G) | reinterpret_cast<uintptr_t>(S_ctx) |
-                        reinterpret_cast<uintptr_t>(S_noctx)) & 15) == 0 &&
-                      (st * esz) % 16 == 0 && (sb * esz) % 16 == 0;
 
     char* ws = static_cast<char*>(workspace);
 
@@ -1152,9 +1150,9 @@ ss_status verify_block_impl(const void* G, const void* S_ctx, const void* S_noct
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t err;
     if (params->dtype == SS_BF16) {
-        err = fast ? launch_all<SS_BF16, 8, 8>(la, ra, pl, ws, s, ev) : launch_all<SS_BF16, 1, 8>(la, ra, pl, ws, s, ev);
+        err = launch_all<SS_BF16, 8>(la, ra, pl, ws, s, ev);
     } else {
-        err = fast ? launch_all<SS_F32, 4, 4>(la, ra, pl, ws, s, ev) : launch_all<SS_F32, 1, 4>(la, ra, pl, ws, s, ev);
+        err = launch_all<SS_F32, 4>(la, ra, pl, ws, s, ev);
     }
     return err == hipSuccess ? SS_OK : SS_ERR_DEVICE;
 }

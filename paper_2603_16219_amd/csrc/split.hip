@@ -516,18 +516,14 @@ ss_status specsteer_cloud_topk(const void* G, const void* S_noctx, const int32_t
     a.G = G; a.Sm = S_noctx; a.row = row; a.out_index = out_index; a.out_value = out_value;
     a.sb = sb; a.st = st; a.B = params->batch; a.kmax = params->k_max; a.V = params->vocab; a.topk = topk;
     a.beta = (double)params->beta;
-    const int esz = params->dtype == SS_BF16 ? 2 : 4;
-    const bool fast = ((reinterpret_cast<uintptr_t>(G) | reinterpret_cast<uintptr_t>(S_noctx)) & 15) == 0 &&
-                      (st * esz) % 16 == 0 && (sb * esz) % 16 == 0;
+    const uintptr_t esz = params->dtype == SS_BF16 ? 2 : 4;  // element alignment is all the 16-byte loads need
+    if (((reinterpret_cast<uintptr_t>(G) | reinterpret_cast<uintptr_t>(S_noctx)) & (esz - 1)) != 0) return SS_ERR_STRIDE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid((unsigned)params->batch), block(kTopThreads);
-    if (params->dtype == SS_BF16) {
-        if (fast) hipLaunchKernelGGL((cloud_topk_kernel<SS_BF16, 8>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((cloud_topk_kernel<SS_BF16, 1>), grid, block, 0, s, a);
-    } else {
-        if (fast) hipLaunchKernelGGL((cloud_topk_kernel<SS_F32, 4>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((cloud_topk_kernel<SS_F32, 1>), grid, block, 0, s, a);
-    }
+    if (params->dtype == SS_BF16)
+        hipLaunchKernelGGL((cloud_topk_kernel<SS_BF16, 8>), grid, block, 0, s, a);
+    else
+        hipLaunchKernelGGL((cloud_topk_kernel<SS_F32, 4>), grid, block, 0, s, a);
     return hipGetLastError() == hipSuccess ? SS_OK : SS_ERR_DEVICE;
 }
 

@@ -69,13 +69,15 @@ def test_workspace_bytes(B):
     assert B.library().specsteer_workspace_bytes(None) == 0
 
 
-def call(B, params, *, null=None, ws=256, ws_bytes=1 << 30):
+def call(B, params, *, null=None, ws=256, ws_bytes=1 << 30, nudge=None):
     """Invoke the entry point with fake, never-dereferenced device addresses."""
     fake = {k: 4096 * (i + 1) for i, k in enumerate(
         ["G", "S_ctx", "S_noctx", "draft", "draft_len", "uniforms", "accepted_len", "next_token", "ntl", "rec",
          "dlp"])}
     if null:
         fake[null] = 0
+    if nudge:
+        fake[nudge[0]] += nudge[1]
     v = lambda k: ctypes.c_void_p(fake[k])
     return B.library().specsteer_verify_block(
         v("G"), v("S_ctx"), v("S_noctx"), v("draft"), v("draft_len"), v("uniforms"),
@@ -114,6 +116,9 @@ def test_argument_errors_are_reported_on_the_host(B):
     assert call(B, P(stride_t=1000, stride_b=4999)) == STRIDE
     assert call(B, P(stride_t=-8)) == STRIDE
     assert call(B, P(stride_t=1008, stride_b=5 * 1008)) == OK
+    for k in ("G", "S_ctx", "S_noctx"):             # bf16 logits must sit on 2-byte boundaries, nothing more
+        assert call(B, P(), nudge=(k, 1)) == STRIDE, k
+        assert call(B, P(), nudge=(k, 2)) == OK, k
     assert call(B, P(), ws=0) == WS
     assert call(B, P(), ws=128) == WS               # not 256-byte aligned
     assert call(B, P(batch=4), ws_bytes=16) == WS   # too small; rejected before any launch

@@ -71,9 +71,9 @@ def test_config_c5_full_size_sampled_sequences(binding, oracle):
                                        (8, 0), (5, 3), (1, 0), (1, 7), (65, 0), (512 * 4 * 3 + 8, 0)])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_ragged_tails_and_alignment(binding, oracle, vocab, pad, dtype):
-    """pad > 0 stores rows with a padded stride (aligned fast path with a partial last vector
-    when the stride is a multiple of 16 bytes); pad == 0 with an odd vocabulary makes rows
-    unaligned and takes the element-wise path."""
+    """pad > 0 stores rows with a padded stride (aligned rows with a partial last vector when the
+    stride is a multiple of 16 bytes); pad == 0 with an odd vocabulary makes most rows start off
+    16-byte boundaries, which the 16-byte loads tolerate."""
     base = W.scaled(W.WORKLOADS["c4"], batch=7, vocab=vocab + pad, k_max=5, name=f"tail{vocab}+{pad}{dtype}")
     import dataclasses
     base = dataclasses.replace(base, dtype=dtype)
@@ -496,7 +496,7 @@ def test_longest_draft_block(binding, oracle):
 
 @pytest.mark.parametrize("dtype,shift", [("bf16", 0), ("f32", 0), ("bf16", 1)])
 def test_largest_vocabulary(binding, oracle, dtype, shift):
-    """V = 2^20, the interface's maximum; shift = 1 moves the rows off 16-byte alignment (element-wise path)."""
+    """V = 2^20, the interface's maximum; shift = 1 moves the rows off 16-byte alignment."""
     import dataclasses
     V = (1 << 20) - shift
     w = dataclasses.replace(W.scaled(W.WORKLOADS["c2"], batch=2, vocab=V, k_max=2, name=f"vmax-{dtype}-{shift}"), dtype=dtype)
@@ -513,7 +513,7 @@ def test_largest_vocabulary(binding, oracle, dtype, shift):
     ("c4", 100, 70000, "bf16"),   # 2 parts of 3 wanted by the chunks
     ("c1", 1, 32000, "f32"),
     ("c5", 33, 65544, "f32"),     # 7 parts
-    ("c3", 16, 151937, "bf16"),   # odd vocabulary: element-wise path, 16 parts
+    ("c3", 16, 151937, "bf16"),   # odd vocabulary: rows off 16-byte boundaries
 ])
 def test_split_recovery_shapes(binding, oracle, name, batch, vocab, dtype):
     import dataclasses
@@ -708,7 +708,7 @@ def test_temperature_and_beta_extremes(binding, oracle, temperature, beta):
 @pytest.mark.parametrize("dtype,vocab", [("bf16", 9000), ("f32", 5003)])
 def test_many_sequences_use_half_size_workgroups(binding, oracle, greedy, beta, dtype, vocab):
     """B >= 512 runs the recovery with two 8-wave workgroups per compute unit: every variant of that kernel
-    (sampled / greedy, steered / beta = 0, vector / element-wise loads), with flagged sequences in the batch."""
+    (sampled / greedy, steered / beta = 0, aligned / unaligned rows), with flagged sequences in the batch."""
     import dataclasses
     w = dataclasses.replace(W.scaled(W.WORKLOADS["c4"], batch=600, vocab=vocab, k_max=5, name=f"half-{dtype}-{beta}-{greedy}"),
                             dtype=dtype, beta=beta)
