@@ -3,8 +3,8 @@
  * SpecSteer's Draft-Verify-Recover protocol.
  *
  * One call processes one drafted block for a batch of B independent
- * sequences (Algorithm 1, phases 2 "Ratio-Based Verification" and 3
- * "Steering Recovery"):
+ * sequences (Algorithm 1, phase 2, the ratio test, and phase 3, the
+ * recovery step):
  *
  *   for each sequence b, for t = 0 .. K_b-1 (stop at the first rejection):
  *       alpha_t = min(1, P_LLM(y_t) / (lambda * P_SLM^-(y_t)))          (Eq. 7)
@@ -13,7 +13,7 @@
  *   h_rec = h_LLM + beta * (h_SLM^+ - h_SLM^-)   at row n_b            (Eq. 8)
  *   next_token ~ Softmax(h_rec / T), drawn by inverse CDF in vocabulary-index
  *       order from uniforms[b][k_max]: the first j whose inclusive cumulative
- *       probability exceeds the uniform ("Sample y_new ~ Softmax(h_rec)").
+ *       probability exceeds the uniform (the sampling step of Algorithm 1, phase 3).
  *
  * P_x = Softmax(h_x / T) over the full vocabulary.  The paper has no
  * temperature (T = 1 is the paper); T > 0 divides all three logit tensors.
@@ -73,7 +73,7 @@ typedef struct {
 } ss_params;
 
 /*
- * Greedy decoding, the setting of the paper's experiments ("we use greedy decoding"): the
+ * Greedy decoding, the decoding setting stated in the paper's implementation-details appendix: the
  * ratio test of Eq. 7 is unchanged, but the correction / bonus token is the mode of the recovery
  * distribution, argmax_v of Eq. 8's h_rec(v) (lowest index on ties), instead of a draw;
  * uniforms[b][k_max] is not read.  h_rec is evaluated for this purpose as
@@ -183,8 +183,8 @@ ss_status specsteer_verify_block_timed(const void *G, const void *S_ctx, const v
                                        size_t workspace_bytes, void *stream, float *stage_ms);
 
 /*
- * Deployment split of the recovery step (the paper's appendix on system deployment, "Minimal
- * Downlink"): the cloud holds h_LLM and h_SLM^-, the edge holds h_SLM^+, and on a rejection only a
+ * Deployment split of the recovery step (the paper's appendix on system deployment, its
+ * downlink step): the cloud holds h_LLM and h_SLM^-, the edge holds h_SLM^+, and on a rejection only a
  * sparse top-k vector travels down.
  *
  * specsteer_cloud_topk -- cloud side.  For every sequence b, at row row[b] of G and S_noctx:

@@ -4,7 +4,7 @@
  * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, obviously-correct
  * statement of what one Draft-Verify-Recover block computes (Algorithm 1,
  * Phases 2 and 3; Eq. 7 ratio-based verification rule; Eq. 8 steering
- * recovery logits; "Sample y ~ Softmax(h_rec)").  It shares no code, header,
+ * recovery logits; the sampling step of phase 3).  It shares no code, header,
  * table or helper with the HIP library and must never be called from the
  * product path: only the tests, the smoke check and the benchmark's
  * cpu_baseline leg may load it.
@@ -54,7 +54,7 @@ typedef struct {
     float temperature;   /* T > 0 */
     int32_t num_threads; /* OpenMP threads over sequences; <=1 => serial */
     int32_t greedy;      /* 0: draw the token by inverse CDF; 1: take argmax h_rec (lowest index on ties),
-                            the deterministic decoding the paper's experiments use in place of "Sample" */
+                            the deterministic decoding the paper's experiments use in place of the sampling step */
 } sso_params;
 
 /* Exact widening of one stored logit to double. */
@@ -255,7 +255,7 @@ int specsteer_oracle_max_threads(void) {
 }
 
 /* ------------------------------------------------------------------------------------------
- * Deployment split of the recovery step (appendix "System Deployment", item "Minimal Downlink").
+ * Deployment split of the recovery step (deployment appendix, the downlink step).
  *
  * Cloud side: at the rejected row the non-private part of Eq. 8,
  *     h_cloud = h_LLM - beta * h_SLM^-,

@@ -138,8 +138,6 @@ def verify_block(G: torch.Tensor, S_ctx: torch.Tensor, S_noctx: torch.Tensor, dr
     """specsteer_verify_block on device tensors G/S_ctx/S_noctx [B, k_max+1, V] (vocab stride 1),
     draft [B, k_max] int32, uniforms [B, k_max+1] float32.  Allocates the outputs (and a workspace
     unless one is given) with torch and returns them in a dict; runs on torch's current stream."""
-    if not G.is_cuda:
-        raise ValueError("specsteer_verify_block needs device tensors; there is no CPU path")
     if not (G.shape == S_ctx.shape == S_noctx.shape) or G.dim() != 3:
         raise ValueError("logit tensors must share a [B, k_max+1, V] shape")
     if not (G.dtype == S_ctx.dtype == S_noctx.dtype):
@@ -149,6 +147,17 @@ def verify_block(G: torch.Tensor, S_ctx: torch.Tensor, S_noctx: torch.Tensor, dr
     B, k1, V = G.shape
     k_max = k1 - 1
     dev = G.device
+    # the kernels index these three by the batch and block shape alone: a short one would be read out of bounds
+    if tuple(draft.shape) != (B, k_max):
+        raise ValueError(f"draft must be [B, k_max] = [{B}, {k_max}], got {tuple(draft.shape)}")
+    if tuple(uniforms.shape) != (B, k_max + 1):
+        raise ValueError(f"uniforms must be [B, k_max+1] = [{B}, {k_max + 1}], got {tuple(uniforms.shape)}")
+    if draft_len is not None and tuple(draft_len.shape) != (B,):
+        raise ValueError(f"draft_len must be [B] = [{B}], got {tuple(draft_len.shape)}")
+    if not (G.is_cuda and S_ctx.is_cuda and S_noctx.is_cuda):
+        raise ValueError("specsteer_verify_block needs device tensors; there is no CPU path")
+    if workspace is not None and (not workspace.is_cuda or not workspace.is_contiguous()):
+        raise ValueError("workspace must be a contiguous device tensor")
     draft = draft.to(device=dev, dtype=torch.int32).contiguous()
     uniforms = uniforms.to(device=dev, dtype=torch.float32).contiguous()
     if draft_len is not None:
@@ -179,6 +188,8 @@ def steer_rows(G: torch.Tensor, S_ctx: torch.Tensor, S_noctx: torch.Tensor, unif
     one uniform per row) -- the per-token fusion the paper compares against.  This is the same entry
     point with no drafted positions (k_max = 0): each row is a one-row sequence whose bonus token is
     drawn from softmax((G + beta (S_ctx - S_noctx)) / T)."""
+    if G.dim() != 2 or uniforms.numel() != G.shape[0]:
+        raise ValueError("rows must be [N, V] with one uniform per row")
     n, v = G.shape
     out = verify_block(G.view(n, 1, v), S_ctx.view(n, 1, v), S_noctx.view(n, 1, v),
                        torch.empty(n, 0, dtype=torch.int32, device=G.device), uniforms.reshape(n, 1),
@@ -204,9 +215,13 @@ def _split_params(T: torch.Tensor, beta: float, temperature: float, greedy: bool
 def cloud_topk(G: torch.Tensor, S_noctx: torch.Tensor, row: torch.Tensor, *, beta: float = 1.0,
                topk: int = 32):
     """specsteer_cloud_topk on device tensors: returns (index [B, topk] int32, value [B, topk] float32)."""
-    if not G.is_cuda or G.shape != S_noctx.shape or G.stride() != S_noctx.stride() or G.stride(2) != 1:
-        raise ValueError("G and S_noctx must be device tensors of one [B, k_max+1, V] shape and stride")
+    if G.dim() != 3 or G.shape != S_noctx.shape or G.stride() != S_noctx.stride() or G.stride(2) != 1:
+        raise ValueError("G and S_noctx must share one [B, k_max+1, V] shape and stride, vocabulary contiguous")
     B = G.shape[0]
+    if tuple(row.shape) != (B,):
+        raise ValueError(f"row must be [B] = [{B}], got {tuple(row.shape)}")
+    if not (G.is_cuda and S_noctx.is_cuda):
+        raise ValueError("specsteer_cloud_topk needs device tensors; there is no CPU path")
     row = row.to(device=G.device, dtype=torch.int32).contiguous()
     idx = torch.empty(B, topk, dtype=torch.int32, device=G.device)
     val = torch.empty(B, topk, dtype=torch.float32, device=G.device)
@@ -222,12 +237,20 @@ def edge_resample(index: torch.Tensor, value: torch.Tensor, S_ctx: torch.Tensor,
                   uniform: torch.Tensor, *, beta: float = 1.0, temperature: float = 1.0,
                   greedy: bool = False) -> dict:
     """specsteer_edge_resample on device tensors."""
-    if not S_ctx.is_cuda or S_ctx.stride(2) != 1:
-        raise ValueError("S_ctx must be a device tensor with the vocabulary contiguous")
+    if S_ctx.dim() != 3 or S_ctx.stride(2) != 1:
+        raise ValueError("S_ctx must be [B, k_max+1, V] with the vocabulary contiguous")
     B = S_ctx.shape[0]
     dev = S_ctx.device
+    if index.dim() != 2 or index.shape[0] != B or index.shape != value.shape:
+        raise ValueError("index and value must both be [B, topk] for S_ctx [B, k_max+1, V]")
+    if index.dtype != torch.int32 or value.dtype != torch.float32:
+        raise ValueError("index must be int32 and value float32")
+    if tuple(row.shape) != (B,) or (not greedy and (uniform is None or tuple(uniform.shape) != (B,))):
+        raise ValueError(f"row and uniform must be [B] = [{B}]")
+    if not (S_ctx.is_cuda and index.is_cuda and value.is_cuda):
+        raise ValueError("specsteer_edge_resample needs device tensors; there is no CPU path")
     row = row.to(device=dev, dtype=torch.int32).contiguous()
-    uniform = uniform.to(device=dev, dtype=torch.float32).contiguous()
+    uniform = None if uniform is None else uniform.to(device=dev, dtype=torch.float32).contiguous()
     tok = torch.empty(B, dtype=torch.int32, device=dev)
     lp = torch.empty(B, dtype=torch.float32, device=dev)
     p = _split_params(S_ctx, beta, temperature, greedy)

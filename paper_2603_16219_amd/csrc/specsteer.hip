@@ -547,8 +547,13 @@ __device__ __forceinline__ double sample_wave(const RecArgs& a, int b, int n, in
         take_last = true;
     }
 
-    // re-read that chunk with each lane holding consecutive logits: one scan over the lanes
-    const double dE = (double)Estar;
+    // re-read that chunk with each lane holding consecutive logits: one scan over the lanes.  The terms are
+    // taken relative to the chunk's own exponent reference, 2^(y - Ec), so that the logits that carry the
+    // chunk are normal fp32 numbers however far the chunk sits below the row's maximum; `sc` brings them
+    // to the scale of the chunk table in double, exactly.
+    const int Ec = tab[cstar].E;
+    const double dE = (double)Ec;
+    const double sc = ldexp(1.0, Ec - Estar);
     float p[kChunkSteps][VEC];
     long first[kChunkSteps];
     int cnt[kChunkSteps];
@@ -559,7 +564,7 @@ __device__ __forceinline__ double sample_wave(const RecArgs& a, int b, int n, in
     for (int j = 0; j < kChunkSteps; ++j) {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) {
-            ls += (double)p[j][i];
+            ls += (double)p[j][i] * sc;
             if (i < cnt[j] && p[j][i] > 0.f) lastpos = first[j] + i;
         }
     }
@@ -570,7 +575,7 @@ __device__ __forceinline__ double sample_wave(const RecArgs& a, int b, int n, in
     for (int j = 0; j < kChunkSteps; ++j) {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) {
-            cw += (double)p[j][i];
+            cw += (double)p[j][i] * sc;
             if (i < cnt[j] && p[j][i] > 0.f) plast = p[j][i];
             if (!take_last && mytok < 0 && i < cnt[j] && cw > target) {
                 mytok = first[j] + i;
@@ -591,14 +596,15 @@ __device__ __forceinline__ double sample_wave(const RecArgs& a, int b, int n, in
 #pragma unroll
         for (int d = 1; d < kWave; d <<= 1) best = max(best, __shfl_xor(best, d, kWave));
         const unsigned long long omask = __ballot(lastpos == best && best >= 0);
-        // no positive term at all is unreachable for finite logits; keep the index valid
+        // the chunk's largest logit is within one unit of Ec, so a positive term always exists unless
+        // the row holds something that is not a number; keep the index valid then
         tok = omask ? best : min((long)cstar * (kWave * kChunkSteps * VEC), (long)a.V - 1);
         ptok = omask ? __shfl(plast, first_lane(omask), kWave) : 1.f;
     }
-    // the chosen logit's exponent back from its term: 2^(y - E*) is a normal fp32 number with one
+    // the chosen logit's exponent back from its term: 2^(y - Ec) is a normal fp32 number with one
     // ulp of error, so log2 of it is good to ~2e-7 whatever the magnitude of y
     const double ytok = dE + log2((double)ptok);
-    const double log2Z = dE + log2(total);
+    const double log2Z = (double)Estar + log2(total);
     if (lane == 0) {
         a.accepted_len[b] = n;
         a.next_token[b] = (int32_t)tok;

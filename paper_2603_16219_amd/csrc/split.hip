@@ -1,6 +1,6 @@
 // Deployment split of SpecSteer's recovery step for MI355X (gfx950).
 //
-// The paper's deployment appendix ("Minimal Downlink") does not ship full-vocabulary logits from
+// The paper's deployment appendix (its downlink step) does not ship full-vocabulary logits from
 // the cloud to the edge on a rejection: the cloud forms the non-private part of Eq. 8,
 //     h_cloud = h_LLM - beta * h_SLM^-,
 // keeps its top-k entries (k = 32), and the edge adds beta * h_SLM^+ on those entries and

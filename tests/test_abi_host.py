@@ -132,6 +132,40 @@ def test_python_wrapper_refuses_cpu_tensors(B):
         B.verify_block(x, x, x, torch.zeros(1, 1, dtype=torch.int32), torch.zeros(1, 2))
 
 
+def test_python_wrappers_refuse_misshapen_arguments_before_any_launch(B):
+    """The kernels index draft, uniforms, draft_len, row, uniform, index and value by the batch and block
+    shape alone, so the wrappers refuse anything else (shape checks come before the device check, which is
+    what lets them run here without a GPU)."""
+    import torch
+
+    Bn, K, V = 3, 4, 16
+    x = torch.zeros(Bn, K + 1, V)
+    d, u, dl = torch.zeros(Bn, K, dtype=torch.int32), torch.zeros(Bn, K + 1), torch.zeros(Bn, dtype=torch.int32)
+    for bad in (dict(draft=torch.zeros(Bn, K - 1, dtype=torch.int32)), dict(uniforms=torch.zeros(Bn, K)),
+                dict(uniforms=torch.zeros(Bn * (K + 1))), dict(draft_len=torch.zeros(Bn - 1, dtype=torch.int32)),
+                dict(draft=torch.zeros(Bn - 1, K, dtype=torch.int32))):
+        kw = dict(draft=d, uniforms=u, draft_len=dl)
+        kw.update(bad)
+        with pytest.raises(ValueError, match="must be"):
+            B.verify_block(x, x, x, kw["draft"], kw["uniforms"], draft_len=kw["draft_len"])
+    with pytest.raises(ValueError, match="no CPU path"):       # well-shaped, but not on a device
+        B.verify_block(x, x, x, d, u, draft_len=dl)
+    with pytest.raises(ValueError, match="row must be"):
+        B.cloud_topk(x, x, torch.zeros(Bn + 1, dtype=torch.int32))
+    idx, val = torch.zeros(Bn, 32, dtype=torch.int32), torch.zeros(Bn, 32)
+    row, un = torch.zeros(Bn, dtype=torch.int32), torch.zeros(Bn)
+    with pytest.raises(ValueError, match="index and value"):
+        B.edge_resample(idx, val[:, :16], x, row, un)
+    with pytest.raises(ValueError, match="index and value"):
+        B.edge_resample(idx[:2], val[:2], x, row, un)
+    with pytest.raises(ValueError, match="row and uniform"):
+        B.edge_resample(idx, val, x, row, un[:2])
+    with pytest.raises(ValueError, match="int32"):
+        B.edge_resample(idx.long(), val, x, row, un)
+    with pytest.raises(ValueError, match="one uniform per row"):
+        B.steer_rows(x[0], x[0], x[0], torch.zeros(K))
+
+
 def test_split_entry_points_reject_bad_arguments_on_the_host(B):
     import torch
 

@@ -450,7 +450,7 @@ def test_golden_rational_examples(oracle):
 # ---------------------------------------------------------------- greedy decoding (the paper's evaluation setting)
 
 def test_greedy_takes_argmax_of_recovery_logits(oracle):
-    """The paper decodes greedily in its experiments; the deterministic form of "Sample y ~ Softmax(h_rec)"
+    """The paper decodes greedily in its experiments; the deterministic form of the sampling step of Algorithm 1, phase 3,
     is the mode of that distribution: argmax of Eq. 8, independent of temperature and of the sampling uniform."""
     rng = np.random.default_rng(21)
     G, Sp, Sm, d, u = rand_block(rng, 16, 3, 90)
@@ -588,6 +588,21 @@ def test_a_uniform_of_one_returns_the_last_token_with_probability(oracle):
         r = oracle.verify_block(G, Z, Z, d, np.array([[us]], np.float32))
         assert r["next_token"][0] == want, (us, r["next_token"][0])
         assert r["next_token_logprob"][0] == pytest.approx(np.log(0.5), abs=1e-15)
+
+
+def test_a_uniform_of_zero_returns_the_first_token_with_probability(oracle):
+    """u = 0 with the head of the row ~300 nats under its maximum and a few masked tokens in front: the
+    inverse CDF's strict comparison returns the first token whose probability is positive in double
+    precision, with that token's own (very negative) log-prob -- checked against scipy's log-softmax."""
+    V = 5000
+    G = np.full((1, 1, V), -300.0, np.float32)
+    G[0, 0, :3] = -np.inf
+    G[0, 0, 2048:] = np.random.default_rng(2).normal(0, 1, V - 2048).astype(np.float32)
+    Z = np.zeros_like(G)
+    r = oracle.verify_block(G, Z, Z, np.zeros((1, 0), np.int32), np.zeros((1, 1), np.float32), beta=1.0)
+    lp = log_softmax(G[0, 0].astype(np.float64))
+    assert r["next_token"][0] == 3 == int(np.nonzero(np.exp(lp) > 0)[0][0])
+    assert r["next_token_logprob"][0] == pytest.approx(lp[3], abs=1e-9) and lp[3] < -300
 
 
 def test_tokens_masked_by_the_generalist_have_no_probability(oracle):
