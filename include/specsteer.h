@@ -157,6 +157,27 @@ ss_status specsteer_verify_block(const void *G, const void *S_ctx, const void *S
                                  void *stream);
 
 /*
+ * specsteer_verify_block for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * operation, arguments, outputs and errors as specsteer_verify_block, but the scratch is a
+ * SS_STATIC_SCRATCH_BYTES array inside the library (one copy on every GPU the library runs on,
+ * held until the process ends) and the call allocates nothing, on the host or on the device.
+ * A block whose specsteer_workspace_bytes(params) exceeds SS_STATIC_SCRATCH_BYTES is refused
+ * with SS_ERR_WORKSPACE before anything is enqueued (use specsteer_verify_block with a workspace
+ * of your own then).  The address of the array is looked up on the first call on each device;
+ * make that first call outside any stream capture.  Every call on one GPU shares that GPU's
+ * array and nothing in it survives a call, so two calls that may overlap in time on one GPU
+ * (two streams, two host threads) race: serialise them, or give all but one a workspace.
+ */
+#define SS_STATIC_SCRATCH_BYTES (8u << 20)
+ss_status specsteer_verify_block_static(const void *G, const void *S_ctx, const void *S_noctx,
+                                        const int32_t *draft, const int32_t *draft_len,
+                                        const float *uniforms, const ss_params *params,
+                                        int32_t *accepted_len, int32_t *next_token,
+                                        float *next_token_logprob, float *recovery_logprobs,
+                                        float *draft_logprobs, void *stream);
+
+/*
  * Benchmark variant of specsteer_verify_block (same operation: Algorithm 1 phases 2-3,
  * Eq. 7, Eq. 8; same arguments, same outputs, same errors).  It brackets each kernel with
  * HIP events recorded on `stream`, WAITS for the last one, and writes the elapsed

@@ -60,6 +60,9 @@ def library() -> ctypes.CDLL:
             + [ctypes.c_size_t, ctypes.c_void_p])
         lib.specsteer_verify_block_timed.restype = ctypes.c_int
         lib.specsteer_verify_block_timed.argtypes = lib.specsteer_verify_block.argtypes + [ctypes.c_void_p]
+        lib.specsteer_verify_block_static.restype = ctypes.c_int
+        lib.specsteer_verify_block_static.argtypes = (
+            [ctypes.c_void_p] * 6 + [ctypes.POINTER(SSParams)] + [ctypes.c_void_p] * 6)
         lib.specsteer_cloud_topk.restype = ctypes.c_int
         lib.specsteer_cloud_topk.argtypes = ([ctypes.c_void_p] * 3 + [ctypes.POINTER(SSParams), ctypes.c_int32]
                                              + [ctypes.c_void_p] * 3)
@@ -128,6 +131,24 @@ def verify_block_raw(G, S_ctx, S_noctx, draft, draft_len, uniforms, params: SSPa
     if rc != _STATUS_OK:
         raise SpecSteerError(rc, status_string(rc))
     return dict(zip(STAGES, (float(x) for x in ms))) if timed else None
+
+
+STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def verify_block_static_raw(G, S_ctx, S_noctx, draft, draft_len, uniforms, params: SSParams, accepted_len,
+                            next_token, next_token_logprob, recovery_logprobs, draft_logprobs,
+                            stream: Optional[int] = None) -> None:
+    """Thin call of specsteer_verify_block_static: the block on the library's own scratch array, no
+    workspace argument and no allocation anywhere in the call."""
+    if stream is None:
+        stream = torch.cuda.current_stream(G.device).cuda_stream
+    rc = library().specsteer_verify_block_static(
+        _ptr(G), _ptr(S_ctx), _ptr(S_noctx), _ptr(draft), _ptr(draft_len), _ptr(uniforms), ctypes.byref(params),
+        _ptr(accepted_len), _ptr(next_token), _ptr(next_token_logprob), _ptr(recovery_logprobs),
+        _ptr(draft_logprobs), ctypes.c_void_p(stream))
+    if rc != _STATUS_OK:
+        raise SpecSteerError(rc, status_string(rc))
 
 
 def verify_block(G: torch.Tensor, S_ctx: torch.Tensor, S_noctx: torch.Tensor, draft: torch.Tensor,

@@ -1163,6 +1163,29 @@ ss_status verify_block_impl(const void* G, const void* S_ctx, const void* S_noct
     return err == hipSuccess ? SS_OK : SS_ERR_DEVICE;
 }
 
+// ------------------------------------------------------------------ library-owned scratch for callers that cannot allocate
+
+// specsteer_verify_block_static runs the block with this array as its workspace.  Every GPU the library runs
+// on holds its own copy until the process ends.  In host code the array's name is only a handle for the lookup
+// below, never an address to hand to a kernel: the device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[SS_STATIC_SCRATCH_BYTES];
+
+// Device address of `scratch` on the current device (looked up with that device current, on the first call
+// there); NULL if the lookup fails.  Host threads may race to fill an entry, all with the same value.
+void* static_scratch_ptr() {
+    static std::atomic<void*> ptrs[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    void* p = ptrs[dev].load(std::memory_order_acquire);
+    if (!p) {
+        void* q = nullptr;
+        if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) return nullptr;
+        ptrs[dev].store(q, std::memory_order_release);
+        p = q;
+    }
+    return p;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1206,6 +1229,21 @@ ss_status specsteer_verify_block_timed(const void* G, const void* S_ctx, const v
     }
     for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
     return st;
+}
+
+ss_status specsteer_verify_block_static(const void* G, const void* S_ctx, const void* S_noctx, const int32_t* draft,
+                                        const int32_t* draft_len, const float* uniforms, const ss_params* params,
+                                        int32_t* accepted_len, int32_t* next_token, float* next_token_logprob,
+                                        float* recovery_logprobs, float* draft_logprobs, void* stream) {
+    if (!params) return SS_ERR_NULL;
+    if (params->dtype != SS_F32 && params->dtype != SS_BF16) return SS_ERR_DTYPE;
+    if (!shape_ok(params)) return SS_ERR_SHAPE;
+    if (make_plan(params).bytes > (size_t)SS_STATIC_SCRATCH_BYTES) return SS_ERR_WORKSPACE;  // block too large for the static scratch
+    void* ws = static_scratch_ptr();
+    if (!ws) return SS_ERR_DEVICE;
+    return verify_block_impl(G, S_ctx, S_noctx, draft, draft_len, uniforms, params, accepted_len, next_token,
+                             next_token_logprob, recovery_logprobs, draft_logprobs, ws, (size_t)SS_STATIC_SCRATCH_BYTES,
+                             stream, nullptr);
 }
 
 int specsteer_first_window(const ss_params* params) {

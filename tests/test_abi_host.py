@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol(lib):
     names = declared_symbols()
     assert names == ["specsteer_cloud_topk", "specsteer_edge_resample", "specsteer_first_window",
                      "specsteer_status_string",
-                     "specsteer_verify_block", "specsteer_verify_block_timed", "specsteer_version",
+                     "specsteer_verify_block", "specsteer_verify_block_static", "specsteer_verify_block_timed", "specsteer_version",
                      "specsteer_workspace_bytes"]
     for n in names:
         assert getattr(lib, n) is not None
@@ -185,6 +185,21 @@ def test_split_entry_points_reject_bad_arguments_on_the_host(B):
     assert cloud(P(beta=float("nan"))) == 4 and edge(P(temperature=0.0)) == 4 and cloud(P(flags=8)) == 4
     assert cloud(P(vocab=0)) == 2
     assert lib.specsteer_cloud_topk(f(1), f(1), f(1), None, 32, f(1), f(1), None) == 1
+
+
+def test_static_scratch_entry_point_checks_its_limit_on_the_host(B):
+    import torch
+
+    lib = B.library()
+    f = lambda x: ctypes.c_void_p(x)
+    call = lambda p: lib.specsteer_verify_block_static(f(4096), f(4096), f(4096), f(4096), None, f(4096), ctypes.byref(p),
+                                                       f(4096), f(4096), None, None, None, None)
+    big = B.make_params(4096, 64, 1 << 20, torch.bfloat16, lam=0.5, beta=1.0, temperature=1.0)
+    assert B.workspace_bytes(big) > B.STATIC_SCRATCH_BYTES and call(big) == 6   # refused before any GPU call
+    assert call(B.make_params(1, 2000, 100, torch.bfloat16, lam=0.5, beta=1.0, temperature=1.0)) == 2
+    assert lib.specsteer_verify_block_static(None, None, None, None, None, None, None, None, None, None, None, None, None) == 1
+    hdr = open(os.path.join(ROOT, "include", "specsteer.h")).read()
+    assert re.search(r"#define SS_STATIC_SCRATCH_BYTES \(8u << 20\)", hdr) and B.STATIC_SCRATCH_BYTES == 8 << 20
 
 
 def test_first_window(B):
