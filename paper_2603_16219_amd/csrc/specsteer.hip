@@ -363,7 +363,8 @@ struct RecArgs {
     double bc;       // beta * log2(e) / T
     double beta;     // beta itself, for the greedy argmax of Eq. 8
     double ln_lambda;
-    double rho;      // (c - fl32(c)) / fl32(c): first-order repair of the row pass's rounded scale
+    double rho;      // (c - fl32(c)) / fl32(c): first-order repair of sums formed with the rounded scale
+    float c_hi;      // fl32(c)
     int greedy;      // SS_FLAG_GREEDY
     int plain;       // beta == 0: no steering term, the specialist rows are not read by the recovery sweep
     // Split recovery (small batches): `parts` workgroups share the recovery row of one sequence.
@@ -405,15 +406,18 @@ __device__ __forceinline__ float ld_steer(const void* row, long e) {
     return PLAIN ? 0.f : ld_elem<DT>(row, e);
 }
 
-// Probability terms 2^(y - E*) of the logits one lane owns in recovery chunk c, laid out so that
+// Probability terms 2^(y - E) of the logits one lane owns in recovery chunk c, laid out so that
 // a lane's logits are consecutive in the vocabulary: lane l holds vectors 4l..4l+3 of the chunk.
 // The pseudo-chunk c == nch holds the < VEC logits past the last full vector, one per lane.
 // cnt[j] says how many entries of p[j] are valid; first[j] is the vocabulary index of p[j][0].
+// PLAIN forms the terms as the sweep did, 2^(fma(h, c_hi, -E)) in fp32.
 template <int DT, int VEC, bool PLAIN>
 __device__ __forceinline__ void chunk_lane_terms(const void* g, const void* sp, const void* sm, long nvec, int tailc,
-                                                 long nch, long c, int lane, double cc, double bc, double dE,
+                                                 long nch, long c, int lane, double cc, double bc, float c_hi, int E,
                                                  float (&p)[kChunkSteps][VEC], long (&first)[kChunkSteps],
                                                  int (&cnt)[kChunkSteps]) {
+    const double dE = (double)E;
+    const float nE = -(float)E;
     typename RawT<DT, VEC>::type rg[kChunkSteps], rp[kChunkSteps], rm[kChunkSteps];
 #pragma unroll
     for (int j = 0; j < kChunkSteps; ++j) {
@@ -439,22 +443,27 @@ __device__ __forceinline__ void chunk_lane_terms(const void* g, const void* sp, 
             unpack_steer<DT, VEC, PLAIN>(rp[j], rm[j], hp, hm);
 #pragma unroll
             for (int i = 0; i < VEC; ++i)
-                p[j][i] = __builtin_amdgcn_exp2f((float)(rec_y(hg[i], hp[i], hm[i], cc, bc) - dE));
+                p[j][i] = PLAIN ? __builtin_amdgcn_exp2f(fmaf(hg[i], c_hi, nE))
+                                : __builtin_amdgcn_exp2f((float)(rec_y(hg[i], hp[i], hm[i], cc, bc) - dE));
         }
     }
     if (c >= nch && lane < tailc) {
         first[0] = nvec * VEC + lane;
         cnt[0] = 1;
-        p[0][0] = __builtin_amdgcn_exp2f((float)(rec_y(ld_elem<DT>(g, first[0]), ld_steer<DT, PLAIN>(sp, first[0]),
-                                                       ld_steer<DT, PLAIN>(sm, first[0]), cc, bc) - dE));
+        const float hg = ld_elem<DT>(g, first[0]);
+        p[0][0] = PLAIN ? __builtin_amdgcn_exp2f(fmaf(hg, c_hi, nE))
+                        : __builtin_amdgcn_exp2f((float)(rec_y(hg, ld_steer<DT, PLAIN>(sp, first[0]),
+                                                               ld_steer<DT, PLAIN>(sm, first[0]), cc, bc) - dE));
     }
 }
 
-// (E, s) mass of recovery chunk c, by one wave: sum over the chunk of 2^(y - E).
+// (E, s) mass of recovery chunk c, by one wave: sum over the chunk of 2^(y - E).  With a steering term the
+// exponent is formed in double (acc_add_rec); PLAIN (beta == 0) has only h_LLM * c to form and takes the
+// row pass's route, one fp32 fma per logit with the rounded scale c_hi, repaired to first order by the caller.
 template <int DT, int VEC, bool GREEDY, bool PLAIN>
 __device__ __forceinline__ Partial chunk_mass(const void* g, const void* sp, const void* sm, long nvec, int tailc,
                                               long nch, long c, int lane, double cc, double bc, double beta,
-                                              Best& best) {
+                                              float c_hi, Best& best) {
     const float cf = (float)cc, bcf = (float)bc;
     Acc acc{kEInit, 0.f};
     if (c < nch) {
@@ -471,20 +480,56 @@ __device__ __forceinline__ Partial chunk_mass(const void* g, const void* sp, con
                 }
             }
         }
+        if (PLAIN && vbase + (long)(kChunkSteps - 1) * kWave < nvec) {  // a full chunk: one accumulate over its 4 vectors
+            float h[kChunkSteps * VEC];
 #pragma unroll
-        for (int j = 0; j < kChunkSteps; ++j) {
-            const long v = vbase + (long)j * kWave;
-            if (v < nvec) {
-                float hg[VEC], hp[VEC], hm[VEC];
-                unpack(rg[j], hg);
-                unpack_steer<DT, VEC, PLAIN>(rp[j], rm[j], hp, hm);
-                acc_add_rec<DT, VEC, GREEDY>(acc, hg, hp, hm, cc, bc, cf, bcf, beta, v * VEC, best);
+            for (int j = 0; j < kChunkSteps; ++j) {
+                float hj[VEC];
+                unpack(rg[j], hj);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) {
+                    h[j * VEC + i] = hj[i];
+                    if (GREEDY && (double)hj[i] > best.v) {
+                        best.v = (double)hj[i];
+                        best.idx = (vbase + (long)j * kWave) * VEC + i;
+                    }
+                }
+            }
+            acc_add_f32<kChunkSteps * VEC>(acc, h, c_hi);
+        } else {
+#pragma unroll
+            for (int j = 0; j < kChunkSteps; ++j) {
+                const long v = vbase + (long)j * kWave;
+                if (v < nvec) {
+                    float hg[VEC], hp[VEC], hm[VEC];
+                    unpack(rg[j], hg);
+                    unpack_steer<DT, VEC, PLAIN>(rp[j], rm[j], hp, hm);
+                    if (PLAIN) {
+#pragma unroll
+                        for (int i = 0; i < VEC; ++i)
+                            if (GREEDY && (double)hg[i] > best.v) {
+                                best.v = (double)hg[i];
+                                best.idx = v * VEC + i;
+                            }
+                        acc_add_f32<VEC>(acc, hg, c_hi);
+                    } else {
+                        acc_add_rec<DT, VEC, GREEDY>(acc, hg, hp, hm, cc, bc, cf, bcf, beta, v * VEC, best);
+                    }
+                }
             }
         }
     } else if (lane < tailc) {
         const long e = nvec * VEC + lane;
         const float hg[1] = {ld_elem<DT>(g, e)}, hp[1] = {ld_steer<DT, PLAIN>(sp, e)}, hm[1] = {ld_steer<DT, PLAIN>(sm, e)};
-        acc_add_rec<DT, 1, GREEDY>(acc, hg, hp, hm, cc, bc, cf, bcf, beta, e, best);
+        if (PLAIN) {
+            if (GREEDY && (double)hg[0] > best.v) {
+                best.v = (double)hg[0];
+                best.idx = e;
+            }
+            acc_add_f32<1>(acc, hg, c_hi);
+        } else {
+            acc_add_rec<DT, 1, GREEDY>(acc, hg, hp, hm, cc, bc, cf, bcf, beta, e, best);
+        }
     }
     return wave_combine(acc);
 }
@@ -509,7 +554,7 @@ __device__ __forceinline__ double sample_wave(const RecArgs& a, int b, int n, in
     const double incl = wave_incl_scan_f64(lsum);
     const double total = wave_last_f64(incl);
     if (GREEDY) {  // the token is already known; only the normaliser is needed
-        const double log2Z = (double)Estar + log2(total);
+        const double log2Z = (double)Estar + log2(total) + (PLAIN ? a.rho : 0.0) * (double)Estar;
         const long tok = min(max(greedy_pick.idx, 0l), (long)a.V - 1);
         if (lane == 0) {
             a.accepted_len[b] = n;
@@ -554,10 +599,13 @@ __device__ __forceinline__ double sample_wave(const RecArgs& a, int b, int n, in
     const int Ec = tab[cstar].E;
     const double dE = (double)Ec;
     const double sc = ldexp(1.0, Ec - Estar);
+    // PLAIN sums were formed with the rounded scale c_hi: exponents come back as y_hi = h * c_hi, the true one
+    // is y_hi * (1 + rho), and the row's log2-sum moves by rho * E* to first order (see acc_add_f32)
+    const double fix = PLAIN ? a.rho : 0.0;
     float p[kChunkSteps][VEC];
     long first[kChunkSteps];
     int cnt[kChunkSteps];
-    chunk_lane_terms<DT, VEC, PLAIN>(g, sp, sm, nvec, tailc, nch, cstar, lane, a.c, a.bc, dE, p, first, cnt);
+    chunk_lane_terms<DT, VEC, PLAIN>(g, sp, sm, nvec, tailc, nch, cstar, lane, a.c, a.bc, a.c_hi, Ec, p, first, cnt);
     double ls = 0.0;
     long lastpos = -1;
 #pragma unroll
@@ -603,8 +651,9 @@ __device__ __forceinline__ double sample_wave(const RecArgs& a, int b, int n, in
     }
     // the chosen logit's exponent back from its term: 2^(y - Ec) is a normal fp32 number with one
     // ulp of error, so log2 of it is good to ~2e-7 whatever the magnitude of y
-    const double ytok = dE + log2((double)ptok);
-    const double log2Z = (double)Estar + log2(total);
+    const double ytok_hi = dE + log2((double)ptok);
+    const double ytok = ytok_hi + fix * ytok_hi;
+    const double log2Z = (double)Estar + log2(total) + fix * (double)Estar;
     if (lane == 0) {
         a.accepted_len[b] = n;
         a.next_token[b] = (int32_t)tok;
@@ -791,7 +840,7 @@ __global__ __launch_bounds__(NT) void accept_recover_kernel(const RecArgs a) {
     const long nch = (nvec + kWave * kChunkSteps - 1) / (kWave * kChunkSteps);
     Best best{-__builtin_huge_val(), 0x7FFFFFFFFFFFFFFFl};
     for (int c = part * NW + wave; c < a.NC; c += NW * S) {
-        const Partial p = chunk_mass<DT, VEC, GREEDY, PLAIN>(g, sp, sm, nvec, tailc, nch, c, lane, a.c, a.bc, a.beta, best);
+        const Partial p = chunk_mass<DT, VEC, GREEDY, PLAIN>(g, sp, sm, nvec, tailc, nch, c, lane, a.c, a.bc, a.beta, a.c_hi, best);
         if (lane == 0) tab[c] = p;
     }
     if (GREEDY) {
@@ -1151,6 +1200,7 @@ ss_status verify_block_impl(const void* G, const void* S_ctx, const void* S_noct
     ra.beta = (double)params->beta;
     ra.greedy = (params->flags & SS_FLAG_GREEDY) ? 1 : 0;
     ra.plain = steer ? 0 : 1;
+    ra.c_hi = c_hi;
     ra.parts = 1; ra.chunk_tab = nullptr; ra.part_best = nullptr; ra.arrive = nullptr;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
