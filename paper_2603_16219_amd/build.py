@@ -14,6 +14,11 @@ HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950",
     # packed-fp32 instructions are switched off for all device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # The logit loads are 16 bytes wide on vector types that promise only element alignment (rows of an odd
+    # vocabulary start anywhere).  This states to the compiler what the code relies on -- wide global loads at
+    # any element-aligned address are legal on this target (the hardware's unaligned access mode, which the
+    # ROCm kernel driver enables) -- instead of leaving it to the toolchain's default for the target.
+    "-Xclang", "-target-feature", "-Xclang", "+unaligned-access-mode",
     "-shared", "-fPIC", "-Wl,-rpath,/opt/rocm/lib",
 ]
 

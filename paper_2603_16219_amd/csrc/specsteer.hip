@@ -25,7 +25,8 @@
 //                  The full log-prob row is a second sweep, taken only on request.
 //                  Batches of at most 128 sequences share each recovery row between
 //                  several workgroups; the one that delivers its chunk masses last
-//                  draws the token (see accept_recover_kernel).
+//                  draws the token (see accept_recover_kernel; hand-over by write-through
+//                  stores and an arrival counter, without cache-wide fences).
 //
 // Precision: logits are widened exactly; sums of exponentials are accumulated in
 // fp32 (one rounding per term, pairwise across lanes), every per-row scalar
@@ -373,6 +374,26 @@ struct RecArgs {
     Best* part_best;      // [B][parts] greedy candidates of the parts
     uint32_t* arrive;     // [B] parts that have delivered; cleared by the first row pass
 };
+
+// Hand-over between workgroups that may run on different XCDs, whose L2 caches are not coherent with each
+// other, without a cache-wide write-back (a device-scope release fence writes the whole L2 back and costs about
+// 40 ns of a serialised resource per fence): the producer writes with device-scope atomic stores, which go
+// through to memory, waits for them to complete, and only then bumps the arrival counter; the workgroup that
+// sees the counter complete reads with device-scope atomic loads.  Nobody ever waits for anybody.
+template <typename T>
+__device__ __forceinline__ void st_dev(T* p, T v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+template <typename T>
+__device__ __forceinline__ T ld_dev(const T* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st_dev_partial(Partial* p, Partial v) {
+    st_dev(reinterpret_cast<unsigned long long*>(p),
+           ((unsigned long long)__float_as_uint(v.s) << 32) | (unsigned long long)(unsigned)v.E);
+}
+__device__ __forceinline__ Partial ld_dev_partial(const Partial* p) {
+    const unsigned long long w = ld_dev(reinterpret_cast<const unsigned long long*>(p));
+    return Partial{(int)(unsigned)(w & 0xFFFFFFFFull), __uint_as_float((unsigned)(w >> 32))};
+}
+// every memory operation this wave has issued so far has completed: s_waitcnt vmcnt(0) lgkmcnt(0)
+__device__ __forceinline__ void wait_stores() { __builtin_amdgcn_s_waitcnt(0x0070); }
 
 // log2 of sum_v 2^(h_v * c) for one row from its slice partials, by one wave: lane k holds
 // slice k (one coalesced load for up to 64 slices), the merge is two DPP reductions.
@@ -780,8 +801,8 @@ __device__ __forceinline__ void wave_best(Best& best) {
 // workgroups share a sequence.  Each repeats steps 2a-2b (cheap), takes every a.parts-th group of
 // 16 chunks in step 3 and delivers its chunk masses to a table in global memory; the part that
 // arrives last (an atomic counter per sequence, no workgroup ever waits for another) runs step 4
-// from the complete table.  The deliveries are made, fenced and counted by one wave, and the
-// last part's reading wave fences before it reads.
+// from the complete table.  The deliveries are made and counted by one wave with write-through stores
+// (st_dev, wait_stores), and the last part reads them with device-scope loads: no cache-wide fence.
 template <int DT, int VEC, bool GREEDY, bool SPLIT, bool PLAIN, int NT>
 __global__ __launch_bounds__(NT) void accept_recover_kernel(const RecArgs a) {
     extern __shared__ double smem_d[];
@@ -856,14 +877,18 @@ __global__ __launch_bounds__(NT) void accept_recover_kernel(const RecArgs a) {
         if (wave == 0) {
             Partial* gtab = a.chunk_tab + (long)b * a.NC;
             for (int c = lane; c < a.NC; c += kWave)
-                if ((c / NW) % S == part) gtab[c] = tab[c];
+                if ((c / NW) % S == part) st_dev_partial(gtab + c, tab[c]);
             if (GREEDY) {
                 best.v = lane < NW ? sh_best_v[lane] : -__builtin_huge_val();
                 best.idx = lane < NW ? sh_best_i[lane] : 0x7FFFFFFFFFFFFFFFl;
                 wave_best(best);
-                if (lane == 0) a.part_best[(long)b * S + part] = best;
+                if (lane == 0) {
+                    Best* o = a.part_best + (long)b * S + part;
+                    st_dev(reinterpret_cast<unsigned long long*>(&o->v), (unsigned long long)__double_as_longlong(best.v));
+                    st_dev(reinterpret_cast<unsigned long long*>(&o->idx), (unsigned long long)best.idx);
+                }
             }
-            __threadfence();  // this wave's deliveries are visible device-wide before it is counted
+            wait_stores();  // this wave's deliveries have reached memory before it is counted
             unsigned prev = 0;
             if (lane == 0) prev = __hip_atomic_fetch_add(a.arrive + b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (lane == 0) sh_last = (prev == (unsigned)(S - 1)) ? 1 : 0;
@@ -871,13 +896,12 @@ __global__ __launch_bounds__(NT) void accept_recover_kernel(const RecArgs a) {
         __syncthreads();
         if (!sh_last) return;
         if (wave == 0) {
-            __threadfence();  // the other parts' deliveries, not a stale cached copy
             const Partial* gtab = a.chunk_tab + (long)b * a.NC;
-            for (int c = lane; c < a.NC; c += kWave) tab[c] = gtab[c];
+            for (int c = lane; c < a.NC; c += kWave) tab[c] = ld_dev_partial(gtab + c);
             if (GREEDY && lane < S) {
-                const Best o = a.part_best[(long)b * S + lane];
-                sh_best_v[lane] = o.v;
-                sh_best_i[lane] = o.idx;
+                const Best* o = a.part_best + (long)b * S + lane;
+                sh_best_v[lane] = __longlong_as_double((long long)ld_dev(reinterpret_cast<const unsigned long long*>(&o->v)));
+                sh_best_i[lane] = (long)ld_dev(reinterpret_cast<const unsigned long long*>(&o->idx));
             }
         }
         __syncthreads();
