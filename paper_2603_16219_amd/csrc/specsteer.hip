@@ -395,17 +395,25 @@ __device__ __forceinline__ Partial ld_dev_partial(const Partial* p) {
 // every memory operation this wave has issued so far has completed: s_waitcnt vmcnt(0) lgkmcnt(0)
 __device__ __forceinline__ void wait_stores() { __builtin_amdgcn_s_waitcnt(0x0070); }
 
-// log2 of sum_v 2^(h_v * c) for one row from its slice partials, by one wave: lane k holds
-// slice k (one coalesced load for up to 64 slices), the merge is two DPP reductions.
-__device__ __forceinline__ double combine_partials_wave(const Partial* p, int NS, int lane, double rho) {
-    Acc q{kEInit, 0.f};
-    if (lane < NS) {
-        const Partial v = p[lane];
-        q.E = v.E;
-        q.s = v.s;
+// log2 of sum_v 2^(h_v * c) for one row from its slice partials, by one lane: the partials are merged in
+// slice order (sixteen loads in flight at a time), so the result does not depend on who computes it.
+__device__ __forceinline__ double combine_partials_lane(const Partial* p, int ns, double rho) {
+    int Em = kEInit;
+    float S = 0.f;
+    for (int k0 = 0; k0 < ns; k0 += 16) {
+        Partial pv[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if (k0 + i < ns) pv[i] = p[k0 + i];
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if (k0 + i < ns) {
+                const int En = max(Em, pv[i].E);
+                S = ldexpf(S, Em - En) + ldexpf(pv[i].s, pv[i].E - En);
+                Em = En;
+            }
     }
-    const Partial m = wave_combine(q);
-    return (double)m.E * (1.0 + rho) + log2((double)m.s);  // E*rho: see acc_add_f32
+    return (double)Em * (1.0 + rho) + log2((double)S);  // E*rho: see acc_add_f32
 }
 
 // PLAIN (beta == 0): the recovery distribution is Softmax(h_LLM / T); the two specialist rows are
@@ -696,7 +704,7 @@ __device__ __forceinline__ const Partial* partials_of(const RecArgs& a, int b, i
 
 // Phase 2 for one sequence by its workgroup of NT threads, on positions [T0, Kt) (those before T0
 // are known to have been accepted):
-//   2a  every (position, tensor) pair gets a wave: merge its slice partials, gather the draft
+//   2a  every (position, tensor) pair gets a lane: merge the row's slice partials, gather the draft
 //       token's logit, leave log P(y_t) in lp[2t + x]        (two memory round trips in all)
 //   2b  wave 0: Eq. 7 on every position, first rejection by ballot -> *sh_n (Kt if none)
 // A draft id outside the vocabulary among those positions sets *sh_bad.  Ends with a barrier.
@@ -704,19 +712,16 @@ template <int DT, int NT>
 __device__ __forceinline__ void ratio_test_block(const RecArgs& a, int b, int T0, int Kt, double* lp, int* sh_n,
                                                  int* sh_bad) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    constexpr int NW = NT / kWave;
     const int kmax = a.kmax, V = a.V;
-    for (int q = 2 * T0 + wave; q < 2 * Kt; q += NW) {
+    for (int q = 2 * T0 + tid; q < 2 * Kt; q += NT) {
         const int t = q >> 1, x = q & 1;
-        const int y = a.draft[(long)b * kmax + t];  // wave-uniform
+        const int y = a.draft[(long)b * kmax + t];
         const bool ok = (y >= 0 && y < V);
         const long off = (long)b * a.sb + (long)t * a.st;
         const float h = ok ? ld_elem<DT>(row_ptr<DT>(x ? a.Sm : a.G, off), y) : 0.f;
-        const double L = combine_partials_wave(partials_of(a, b, t, x), t < a.t1 ? a.NS : a.NS2, lane, a.rho);
-        if (lane == 0) {
-            lp[q] = kLn2 * ((double)h * a.c - L);
-            if (!ok) *sh_bad = 1;
-        }
+        const double L = combine_partials_lane(partials_of(a, b, t, x), t < a.t1 ? a.NS : a.NS2, a.rho);
+        lp[q] = kLn2 * ((double)h * a.c - L);
+        if (!ok) *sh_bad = 1;
     }
     __syncthreads();
     if (wave == 0) {
@@ -742,8 +747,10 @@ __device__ __forceinline__ void ratio_test_block(const RecArgs& a, int b, int T0
 // rejection): its later rows are never scored and its first-rejection index is final.  Every
 // draft id of the sequence is range-checked here, so a sequence is flagged exactly as in the
 // one-pass schedule.
+constexpr int kVerdictThreads = 64;  // one wave per sequence: a lane per (position, tensor) pair is plenty
+
 template <int DT>
-__global__ __launch_bounds__(kRecThreads) void verdict_kernel(const RecArgs a, int32_t* alive, int32_t* flagged,
+__global__ __launch_bounds__(kVerdictThreads) void verdict_kernel(const RecArgs a, int32_t* alive, int32_t* flagged,
                                                               int32_t* first_rej) {
     extern __shared__ double smem_d[];
     __shared__ int sh_n, sh_bad;
@@ -758,7 +765,7 @@ __global__ __launch_bounds__(kRecThreads) void verdict_kernel(const RecArgs a, i
     __syncthreads();
     if (!bad_len) {
         bool oob = false;
-        for (int t = tid; t < K; t += kRecThreads) {
+        for (int t = tid; t < K; t += kVerdictThreads) {
             const int y = a.draft[(long)b * kmax + t];
             oob = oob || y < 0 || y >= V;
         }
@@ -766,7 +773,7 @@ __global__ __launch_bounds__(kRecThreads) void verdict_kernel(const RecArgs a, i
     }
     __syncthreads();
     const int Kt = sh_bad ? 0 : min(K, a.t1);
-    ratio_test_block<DT, kRecThreads>(a, b, 0, Kt, smem_d, &sh_n, &sh_bad);
+    ratio_test_block<DT, kVerdictThreads>(a, b, 0, Kt, smem_d, &sh_n, &sh_bad);
     if (tid == 0) {
         const bool bad = sh_bad != 0;
         alive[b] = (!bad && sh_n == Kt && K > a.t1) ? 1 : 0;
@@ -1133,7 +1140,7 @@ hipError_t launch_all(LseArgs la, RecArgs ra, const Plan& pl, char* ws, hipStrea
                                           ragged ? 0 : t1, off1, partial1, (long)B * t1, stream);
     mark(1);
     if (two_pass)
-        hipLaunchKernelGGL((verdict_kernel<DT>), dim3((unsigned)B), dim3(kRecThreads), (size_t)2 * kmax * sizeof(double),
+        hipLaunchKernelGGL((verdict_kernel<DT>), dim3((unsigned)B), dim3(kVerdictThreads), (size_t)2 * kmax * sizeof(double),
                            stream, ra, alive, flagged, first_rej);
     mark(2);
     if (two_pass) {
