@@ -189,9 +189,10 @@ def measure(binding, W, w, sets, dev, *, steps, warmup, mode="verify", full_rows
         # G / S_noctx bonus rows of fully accepted sequences (a rejected row was already read by a row pass)
         step_bytes += (2.0 * rows + B + 2.0 * n_bonus) * V * esz / n_timed
         bonus_frac += n_bonus / B / n_timed
-    lse_ms = stage["row_pass1"] + stage["row_pass2"]
-    lse_gbs = lse_bytes / (lse_ms * 1e-3) / 1e9 if lse_ms > 0 else 0.0
     n_lse = 2 if (not rows_mode and t1 < kmax) else 1  # launches of the row-pass kernel per step
+    # a stage that launches nothing still measures the ~5 us of its event pair: only passes that ran are counted
+    lse_ms = stage["row_pass1"] + (stage["row_pass2"] if n_lse == 2 else 0.0)
+    lse_gbs = lse_bytes / (lse_ms * 1e-3) / 1e9 if lse_ms > 0 else 0.0
     if rows_mode:
         # no row pass: the recovery sweep is the dominant (only) kernel; it reads 3 rows per row, 1 when beta = 0
         per_row = (1 if mode == "draft_sample" else 3) * V * esz
