@@ -60,3 +60,36 @@ def binding_mod():
     assert torch.cuda.is_available(), "GPU tests need a device"
     b.library()
     return b
+
+
+def test_static_scratch_entry_point_inside_a_hip_graph(binding_mod):
+    """The callers this entry point is for: the block captured in a HIP graph (no allocation, no workspace argument),
+    replayed on new contents of the same buffers, with eager work and synchronisations between the replays; every replay
+    must equal the workspace entry point's direct result bit for bit."""
+    binding = binding_mod
+    w = W.scaled(W.WORKLOADS["c4"], batch=48, vocab=60000, name="static-graph")
+    inp = W.generate(w, "cuda")
+    B, K, V = w.batch, w.k_max, w.vocab
+    p = binding.make_params(B, K, V, torch.bfloat16, lam=w.lam, beta=w.beta, temperature=w.temperature)
+    mk = lambda dt: torch.full((B,), -7, dtype=dt, device="cuda")
+    acc, tok, lp = mk(torch.int32), mk(torch.int32), mk(torch.float32)
+    args = (inp["G"], inp["S_ctx"], inp["S_noctx"], inp["draft"], inp["draft_len"], inp["uniforms"], p)
+    binding.verify_block_static_raw(*args, acc, tok, lp, None, None)   # first call on the device: outside any capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        binding.verify_block_static_raw(*args, acc, tok, lp, None, None)
+    ws = torch.empty(binding.workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    acc2, tok2, lp2 = mk(torch.int32), mk(torch.int32), mk(torch.float32)
+    for rnd in range(4):
+        fresh = W.generate(w, "cuda", seed_shift=rnd + 1)
+        for k in ("G", "S_ctx", "S_noctx", "draft", "uniforms", "draft_len"):
+            inp[k].copy_(fresh[k])
+        acc.fill_(-7)
+        tok.fill_(-7)
+        g.replay()
+        torch.cuda.synchronize()
+        binding.verify_block_raw(*args, acc2, tok2, lp2, None, None, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(acc, acc2) and torch.equal(tok, tok2) and torch.equal(lp, lp2), rnd
+        assert torch.all(acc >= 0)
