@@ -15,11 +15,12 @@
 //                  LDS at kernel start (prep_rows does it once in global memory for
 //                  batches too large for LDS).
 //   accept_recover one 16-wave workgroup per sequence.  Each (position, tensor) pair
-//                  gets a wave that merges the slice partials and gathers the draft
+//                  gets a lane that merges the row's slice partials and gathers the draft
 //                  token's logit; wave 0 applies the ratio test and finds the first
 //                  rejection with a ballot.  All waves then stream the three logit rows
 //                  of the rejected (or bonus) position once, forming the recovery
-//                  exponent in double, and record one (E, s) mass per 2048-logit chunk
+//                  exponent in double (in fp32, as the row pass does, when beta == 0 leaves
+//                  no steering term), and record one (E, s) mass per 2048-logit chunk
 //                  in LDS.  A double-precision scan over the chunk masses locates the
 //                  chunk holding u*Z; only that chunk is read again to pick the token.
 //                  The full log-prob row is a second sweep, taken only on request.
