@@ -63,11 +63,21 @@ def read_traffic(workload: str):
             f"profiles/{os.path.basename(path)}")
 
 
-def bench_split(args, w, sets, dev) -> int:
+def rows_view(torch, w, s, mode, dev):
+    """Every row of a verify workload as a one-row sequence with no drafted position (views, no copy)."""
+    n_rows = w.batch * (w.k_max + 1)
+    r = {k: s[k].view(n_rows, 1, w.vocab) for k in ("G", "S_ctx", "S_noctx")}
+    if mode == "draft_sample":
+        r["G"] = r["S_noctx"] = r["S_ctx"]
+    r["draft"] = torch.empty(n_rows, 0, dtype=torch.int32, device=dev)
+    r["draft_len"] = None
+    r["uniforms"] = s["uniforms"].reshape(n_rows, 1)
+    return r
+
+
+def measure_split(binding, w, sets, dev, *, steps, warmup) -> dict:
     """Deployment split: cloud top-k at one (seeded) row per sequence, then the edge resampling."""
     import torch
-
-    from paper_2603_16219_amd import binding
 
     B, V = w.batch, w.vocab
     esz = 2 if w.dtype == "bf16" else 4
@@ -81,18 +91,18 @@ def bench_split(args, w, sets, dev) -> int:
         return binding.edge_resample(idx, val, s["S_ctx"], rows[i % len(sets)], us[i % len(sets)], beta=w.beta,
                                      temperature=w.temperature)
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         step(i)
     torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    ms = (time.perf_counter() - t0) / steps * 1e3
     # the cloud kernel alone: one pair of torch events on the current stream (the library launches there)
     # around a run of back-to-back launches, so that host-side call overhead hides behind the queue
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    n_timed = max(args.steps, 20)
+    n_timed = max(steps, 20)
     torch.cuda.synchronize()
     e0.record()
     for i in range(n_timed):
@@ -102,14 +112,23 @@ def bench_split(args, w, sets, dev) -> int:
     e1.synchronize()
     kms = e0.elapsed_time(e1) / n_timed
     nbytes = 2.0 * B * V * esz
+    return {"ms_per_step": ms, "rows_per_s": B / (ms * 1e-3), "kernel_ms": kms, "bytes": nbytes,
+            "gbs": nbytes / (kms * 1e-3) / 1e9}
+
+
+def bench_split(args, w, sets, dev) -> int:
+    from paper_2603_16219_amd import binding
+
+    m = measure_split(binding, w, sets, dev, steps=args.steps, warmup=args.warmup)
     out = {
-        "metric": "top-32 downlink rows/sec", "value": B / (ms * 1e-3), "unit": "rows/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f64", "data": "synthetic",
-        "config": {"workload": describe(w), "mode": "cloud_topk", "topk": 32, "logits_dtype": w.dtype},
-        "roofline": {"bound": "hbm", "kernel": "cloud_topk_kernel", "achieved": nbytes / (kms * 1e-3) / 1e9,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": nbytes / (kms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                     "traffic": None, "algorithmic_bytes_per_launch": nbytes, "avg_launch_ms": kms},
+        "metric": "top-32 downlink rows/sec", "value": m["rows_per_s"], "unit": "rows/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": m["ms_per_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": describe(w), "mode": "cloud_topk", "topk": 32, "logits_dtype": w.dtype,
+                   "kernel_source_sha256": kernel_source_hash()},
+        "roofline": {"bound": "hbm", "kernel": "cloud_topk_kernel", "achieved": m["gbs"],
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": m["gbs"] / HBM_PEAK_GBS,
+                     "traffic": None, "algorithmic_bytes_per_launch": m["bytes"], "avg_launch_ms": m["kernel_ms"]},
     }
     print(json.dumps(out), flush=True)
     return 0
@@ -227,7 +246,7 @@ def main() -> int:
     ap.add_argument("--sets", type=int, default=2, help="rotating input sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
-                    help="skip the one-pass schedule and the other workloads (the short sub-records of the line)")
+                    help="skip the one-pass schedule, the other modes and the other workloads (the short sub-records of the line)")
     ap.add_argument("--dtype", choices=["bf16", "f32"], default=None,
                     help="store the workload's logits in this type instead of its own (same recipe, rounded to it)")
     ap.add_argument("--graph", action="store_true",
@@ -280,15 +299,7 @@ def main() -> int:
         return bench_split(args, w, sets, dev)
     rows_mode = args.mode in ("steer_rows", "draft_sample")
     if rows_mode:
-        for s_ in sets:
-            n_rows = w.batch * (w.k_max + 1)
-            for k_ in ("G", "S_ctx", "S_noctx"):
-                s_[k_] = s_[k_].view(n_rows, 1, V)
-            if args.mode == "draft_sample":
-                s_["G"] = s_["S_noctx"] = s_["S_ctx"]
-            s_["draft"] = torch.empty(n_rows, 0, dtype=torch.int32, device=dev)
-            s_["draft_len"] = None
-            s_["uniforms"] = s_["uniforms"].reshape(n_rows, 1)
+        sets = [rows_view(torch, w, s_, args.mode, dev) for s_ in sets]
 
     if args.calibrate_copy:
         # a plain elementwise copy of known size: reads 1 GiB, writes 1 GiB per launch
@@ -403,7 +414,23 @@ def main() -> int:
         # the same workload on the one-pass schedule (every valid row scored), a short second loop
         fr = measure(binding, W, w, sets, dev, steps=min(args.steps, 20), warmup=min(args.warmup, 5), full_rows=True)
         out["full_rows"] = brief(fr)
-        del fr, m
+        # the modes that run on the same kernels, on the same logits: short loops
+        short = dict(steps=min(args.steps, 20), warmup=min(args.warmup, 5))
+        modes = {}
+        gm = measure(binding, W, w, sets, dev, mode="greedy", **short)
+        modes["greedy"] = {"us_per_step": round(gm["ms_per_step"] * 1e3, 2), "positions_per_s": round(gm["value"], 1)}
+        for md in ("steer_rows", "draft_sample"):
+            rm = measure(binding, W, w, [rows_view(torch, w, s_, md, dev) for s_ in sets], dev, mode=md, **short)
+            modes[md] = {"us_per_step": round(rm["ms_per_step"] * 1e3, 2), "rows_per_s": round(rm["value"], 1),
+                         "kernel_us": round(rm["avg_launch_ms"] * 1e3, 2), "kernel_GB/s": round(rm["lse_gbs"], 1),
+                         "kernel_frac_of_peak": round(rm["lse_gbs"] / HBM_PEAK_GBS, 4)}
+            del rm
+        sm = measure_split(binding, w, sets, dev, **short)
+        modes["cloud_topk"] = {"us_per_step": round(sm["ms_per_step"] * 1e3, 2), "rows_per_s": round(sm["rows_per_s"], 1),
+                               "kernel_us": round(sm["kernel_ms"] * 1e3, 2), "kernel_GB/s": round(sm["gbs"], 1),
+                               "kernel_frac_of_peak": round(sm["gbs"] / HBM_PEAK_GBS, 4)}
+        out["modes"] = modes
+        del fr, m, gm
         del sets, ws, acc, tok, tlp
         torch.cuda.empty_cache()
         # the other workloads: microseconds per step in the launch configuration the tests verify
